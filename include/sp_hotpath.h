@@ -1,0 +1,164 @@
+/*
+ * sp_hotpath.h -- C ABI of the per-GPU hot path of a Ulysses-style
+ * sequence-parallel transformer layer on one MI355X (gfx950).
+ *
+ * The paper (Section 2, Figure 1) describes the step this library serves:
+ * outside attention a device holds part of the sequence with all heads,
+ * [S/P, H, D]; an all-to-all re-shards to the whole sequence with a subset of
+ * the heads, [S, H/P, D]; attention runs locally on those heads; a second
+ * all-to-all restores the first layout.  This library is what one device
+ * executes around and between those two exchanges: the local re-layout that
+ * makes the P per-peer messages contiguous (and its inverse), and causal
+ * grouped-query attention, forward and backward, over the full sequence for
+ * the device's head shard.  The exchange itself is not part of it.
+ *
+ * Conventions, all entry points
+ *   - Every pointer is a DEVICE pointer unless stated otherwise, 16-byte
+ *     aligned; tensors are dense row-major with the head dim innermost.
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and never synchronises: a call validates its arguments on the
+ *     host, enqueues kernels on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and returns.
+ *   - Outputs are fully overwritten; they need no pre-clearing.
+ *   - Inputs and outputs must not overlap.
+ *   - Errors are return codes.  Argument errors are found before any launch
+ *     (no GPU is needed to get them); a failed launch gives SP_ERR_LAUNCH.
+ *   - Empty problems (a zero extent) return SP_OK without launching.
+ *   - No global mutable state: calls from several host threads are safe as
+ *     long as they do not share output or workspace buffers.
+ *   - bf16 tensors are `uint16_t`-sized elements passed as `const void*`.
+ */
+#ifndef SP_HOTPATH_H
+#define SP_HOTPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_NULL = 1,        /* a required pointer is NULL                        */
+    SP_ERR_SHAPE = 2,       /* negative extent, H % P != 0, Hq % Hkv != 0, ...   */
+    SP_ERR_UNSUPPORTED = 3, /* head dim or element size outside the supported set */
+    SP_ERR_WORKSPACE = 4,   /* workspace smaller than the matching *_bytes query  */
+    SP_ERR_ALIGN = 5,       /* a pointer is not 16-byte aligned                   */
+    SP_ERR_LAUNCH = 6       /* the HIP runtime refused a launch                   */
+} sp_status;
+
+/* Static, human-readable name of a status code.  Never NULL. */
+const char* sp_status_str(sp_status s);
+
+/* Version of this ABI (bumped on any signature change). */
+int32_t sp_abi_version(void);
+
+/* ---------------------------------------------------------------------------
+ * Re-layout before the first all-to-all (Section 2: the exchange re-shards
+ * from the sequence dimension to the head dimension; Section 3.1, challenge 1:
+ * the exchange needs token buffers of a size fixed by batch, sequence length
+ * and model dimension).
+ *
+ *   in  [B, S_l, H, D]      this device's S_l = S/P tokens, all H heads
+ *   out [B, P*S_l, H/P, D]  out[b, p*S_l + s, j, :] = in[b, s, p*(H/P) + j, :]
+ *
+ * Rows p*S_l .. (p+1)*S_l-1 of `out` are the contiguous message for peer p
+ * (heads are split into P contiguous groups, so a query-head group and its
+ * key/value head land on the same peer when both head counts divide by P).
+ * Seen from the receiving side, the P messages a device gets, concatenated in
+ * source-rank order, are its [S, H/P, D] attention-side tensor.
+ *
+ * A pure byte permutation, bit-exact for any element contents.
+ * elem_bytes in {2, 4}; D*elem_bytes must be a multiple of 16; H % P == 0.
+ * ------------------------------------------------------------------------- */
+sp_status sp_pack_seq_to_head(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
+                              int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream);
+
+/* Exact inverse, applied after the second all-to-all (Section 2: tokens go
+ * "back to their original input sizes"); it is also the gradient of the pack
+ * (Section 3.1: every inserted node needs its conjugate gradient operator).
+ *
+ *   in  [B, P*S_l, H/P, D]
+ *   out [B, S_l, H, D]      out[b, s, p*(H/P) + j, :] = in[b, p*S_l + s, j, :]
+ */
+sp_status sp_unpack_head_to_seq(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
+                                int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Causal grouped-query attention, forward (Section 2: each device computes
+ * attention locally on its heads over the entire context; Section 3.1,
+ * challenge 3: the causal mask is part of the model; Section 4: evaluated
+ * models use grouped-query or full attention).
+ *
+ *   q [B, S, Hq, D], k, v [B, S, Hkv, D]   bf16
+ *   o [B, S, Hq, D]                        bf16 (round-to-nearest-even)
+ *   lse [B, Hq, S]                         fp32, natural log, scale included
+ *
+ * Query head a reads key/value head a / (Hq/Hkv).  Key j is visible to query
+ * i iff j <= i.  s_ij = softmax_scale * q_i.k_j; softmax_scale <= 0 selects
+ * 1/sqrt(D).  Contractions run in bf16 MFMA with fp32 accumulation; the
+ * softmax runs in fp32.  D in {64, 128}; Hq % Hkv == 0; S < 2^31.
+ * ------------------------------------------------------------------------- */
+sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                      int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                      float softmax_scale, void* hip_stream);
+
+/* Bytes of device workspace sp_attn_bwd / sp_attn_varlen_fwd / sp_attn_varlen_bwd
+ * need for these extents (T = B*S for the dense call, total tokens for varlen;
+ * n_docs = 0 for the dense call).  Returns 0 for invalid arguments. */
+size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_t Hkv, int32_t D,
+                                   int32_t n_docs);
+size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                                          int32_t n_docs);
+
+/* ---------------------------------------------------------------------------
+ * Backward of sp_attn_fwd (Section 3.1: the rewritten graph must stay correct
+ * in the backward pass; Section 4.4: the backward is where recomputation
+ * under activation checkpointing is paid).
+ *
+ *   inputs : q, k, v, o (as written by the forward), lse, dO [B, S, Hq, D] bf16
+ *   outputs: dq [B, S, Hq, D], dk, dv [B, S, Hkv, D]  bf16
+ *   workspace: >= sp_attn_bwd_workspace_bytes(...) bytes, contents undefined
+ *              on entry and exit (holds Delta_i = dO_i.O_i in fp32).
+ *
+ *   dV_j = sum_{a in group} sum_{i>=j} P_ij dO_i,  dP_ij = dO_i.v_j,
+ *   dS_ij = P_ij (dP_ij - Delta_i),
+ *   dQ_i = scale sum_{j<=i} dS_ij k_j,  dK_j = scale sum_{a in group} sum_{i>=j} dS_ij q_i.
+ *
+ * No atomics: results are bitwise reproducible run to run.
+ * ------------------------------------------------------------------------- */
+sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                      const void* dO, void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
+                      int32_t D, float softmax_scale, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Packed variable-length documents (not in the paper; the block-diagonal form
+ * of the same operator, as long-context training batches are usually packed).
+ *
+ *   q [T, Hq, D], k, v [T, Hkv, D], o [T, Hq, D] bf16; lse [Hq, T] fp32
+ *   cu_seqlens: DEVICE int32 [n_docs+1], cu[0] = 0, non-decreasing,
+ *               cu[n_docs] = T.  Rows [cu[t], cu[t+1]) are document t; key j is
+ *               visible to query i iff both are in one document and j <= i.
+ *               Empty documents are allowed.  The contents are read on the
+ *               device only; a malformed array is undefined behaviour confined
+ *               to the output values (all accesses stay inside [0, T)).
+ *   max_seqlen: host upper bound on the longest document (a hint; 0 = T).
+ *   workspace : >= the matching *_workspace_bytes query.
+ * ------------------------------------------------------------------------- */
+sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o,
+                             const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP_HOTPATH_H */

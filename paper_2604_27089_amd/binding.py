@@ -1,0 +1,189 @@
+"""ctypes binding of libsp_hotpath.so: argument marshalling only.
+
+Function names and argument order mirror include/sp_hotpath.h.  Tensors are
+torch CUDA(HIP) tensors used purely as device memory; the stream is torch's
+current stream unless one is given.  There is no fallback: a missing library
+raises ImportError at first use, and a non-zero status raises SpError.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsp_hotpath.so")
+
+SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_ALIGN, SP_ERR_LAUNCH = range(7)
+
+EXPORTS = (
+    "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
+    "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd",
+    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd",
+)
+
+
+class SpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_str(code)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_27089_amd.build` "
+                          "(there is no CPU or PyTorch fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, i32, f32, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_float, c.c_size_t
+    L.sp_status_str.restype = c.c_char_p; L.sp_status_str.argtypes = [c.c_int]
+    L.sp_abi_version.restype = i32; L.sp_abi_version.argtypes = []
+    for name in ("sp_pack_seq_to_head", "sp_unpack_head_to_seq"):
+        f = getattr(L, name); f.restype = c.c_int
+        f.argtypes = [vp, vp, i64, i64, i64, i64, i32, i32, vp]
+    L.sp_attn_fwd.restype = c.c_int
+    L.sp_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, f32, vp]
+    L.sp_attn_bwd_workspace_bytes.restype = sz
+    L.sp_attn_bwd_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
+    L.sp_attn_varlen_fwd_workspace_bytes.restype = sz
+    L.sp_attn_varlen_fwd_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+    L.sp_attn_bwd.restype = c.c_int
+    L.sp_attn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, f32, vp]
+    L.sp_attn_varlen_fwd.restype = c.c_int
+    L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
+    L.sp_attn_varlen_bwd.restype = c.c_int
+    L.sp_attn_varlen_bwd.argtypes = [vp] * 10 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def status_str(code: int) -> str:
+    return lib().sp_status_str(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != SP_OK:
+        raise SpError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+# --------------------------------------------------------------------------- re-layout
+def sp_pack_seq_to_head(x: torch.Tensor, P: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x [B, S_l, H, D] -> out [B, P*S_l, H/P, D]."""
+    B, S_l, H, D = x.shape
+    if out is None:
+        out = torch.empty((B, P * S_l, H // max(P, 1) if P > 0 else H, D), dtype=x.dtype, device=x.device)
+    _check(lib().sp_pack_seq_to_head(_ptr(x), _ptr(out), B, S_l, H, D, P, x.element_size(), _stream(stream)),
+           "sp_pack_seq_to_head")
+    return out
+
+
+def sp_unpack_head_to_seq(y: torch.Tensor, P: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """y [B, P*S_l, h, D] -> out [B, S_l, P*h, D]."""
+    B, PS, h, D = y.shape
+    S_l, H = PS // P, h * P
+    if out is None:
+        out = torch.empty((B, S_l, H, D), dtype=y.dtype, device=y.device)
+    _check(lib().sp_unpack_head_to_seq(_ptr(y), _ptr(out), B, S_l, H, D, P, y.element_size(), _stream(stream)),
+           "sp_unpack_head_to_seq")
+    return out
+
+
+# --------------------------------------------------------------------------- attention
+def sp_attn_fwd(q, k, v, softmax_scale: float = 0.0, o=None, lse=None, stream=None):
+    """q [B,S,Hq,D], k,v [B,S,Hkv,D] bf16 -> (o [B,S,Hq,D] bf16, lse [B,Hq,S] fp32)."""
+    B, S, Hq, D = q.shape
+    Hkv = k.shape[2]
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device)
+    _check(lib().sp_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, S, Hq, Hkv, D,
+                             float(softmax_scale), _stream(stream)), "sp_attn_fwd")
+    return o, lse
+
+
+def sp_attn_bwd_workspace_bytes(B, S_or_T, Hq, Hkv, D, n_docs=0) -> int:
+    return int(lib().sp_attn_bwd_workspace_bytes(B, S_or_T, Hq, Hkv, D, n_docs))
+
+
+def sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs) -> int:
+    return int(lib().sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty((max(int(nbytes), 256),), dtype=torch.uint8, device=device)
+
+
+def sp_attn_bwd(q, k, v, o, lse, do, softmax_scale: float = 0.0, dq=None, dk=None, dv=None,
+                workspace=None, stream=None):
+    """Returns (dq, dk, dv), bf16, shaped like q, k, v."""
+    B, S, Hq, D = q.shape
+    Hkv = k.shape[2]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    if workspace is None:
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0), q.device)
+    _check(lib().sp_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq), _ptr(dk),
+                             _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
+                             float(softmax_scale), _stream(stream)), "sp_attn_bwd")
+    return dq, dk, dv
+
+
+def sp_attn_varlen_fwd(q, k, v, cu_seqlens, max_seqlen: int = 0, softmax_scale: float = 0.0, o=None,
+                       lse=None, workspace=None, stream=None):
+    """q [T,Hq,D], k,v [T,Hkv,D]; cu_seqlens device int32 [n_docs+1] -> (o, lse [Hq,T])."""
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    n_docs = cu_seqlens.numel() - 1
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=q.device) if lse is None else lse
+    if workspace is None:
+        workspace = _workspace(sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs), q.device)
+    _check(lib().sp_attn_varlen_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(cu_seqlens), n_docs,
+                                    int(max_seqlen), T, Hq, Hkv, D, float(softmax_scale), _ptr(workspace),
+                                    workspace.numel(), _stream(stream)), "sp_attn_varlen_fwd")
+    return o, lse
+
+
+def sp_attn_varlen_bwd(q, k, v, o, lse, do, cu_seqlens, max_seqlen: int = 0, softmax_scale: float = 0.0,
+                       dq=None, dk=None, dv=None, workspace=None, stream=None):
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    n_docs = cu_seqlens.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    if workspace is None:
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs), q.device)
+    _check(lib().sp_attn_varlen_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
+                                    _ptr(dk), _ptr(dv), _ptr(cu_seqlens), n_docs, int(max_seqlen), T, Hq,
+                                    Hkv, D, float(softmax_scale), _ptr(workspace), workspace.numel(),
+                                    _stream(stream)), "sp_attn_varlen_bwd")
+    return dq, dk, dv
+
+
+def default_scale(D: int) -> float:
+    return 1.0 / math.sqrt(D)

@@ -1,0 +1,91 @@
+// Sequence<->head re-layout around the all-to-all (paper Section 2, Figure 1:
+// the exchange toggles activations between [S/P, all heads] and
+// [S, heads/P]; Section 3.1 challenge 1: its buffers are sized by batch,
+// sequence and model dimension).
+//
+// pack   (to_head):  out[b, p*S_l + s, j, :] = in[b, s, p*h + j, :]
+// unpack (to_seq) :  out[b, s, p*h + j, :]   = in[b, p*S_l + s, j, :]
+//
+// Both are permutations of runs of h*D*elem_bytes contiguous bytes, moved as
+// 16-byte vectors.  The kernel walks the OUTPUT linearly (fully coalesced
+// stores) and gathers; a gather run is at least 256 bytes long for every
+// workload shape, so reads are coalesced too.  HBM-bound: one read and one
+// write of every byte, no reuse, hence non-temporal accesses.
+#include "sp_common.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 8;  // 16-byte vectors in flight per thread
+
+// n_vec   : total 16-byte vectors
+// run     : vectors per contiguous run (h * D * elem_bytes / 16)
+// S_l, P  : tokens per rank, ranks
+// TO_HEAD : pack if true, unpack otherwise
+// IDX     : uint32_t when every vector index fits 32 bits (cheap divisions)
+template <bool TO_HEAD, typename IDX>
+__global__ __launch_bounds__(kThreads) void relayout_kernel(const u32x4* __restrict__ in,
+                                                           u32x4* __restrict__ out,
+                                                           uint64_t n_vec, uint32_t run,
+                                                           uint32_t S_l, uint32_t P) {
+    const IDX base = (IDX)blockIdx.x * (IDX)(kThreads * kUnroll) + (IDX)threadIdx.x;
+    u32x4 val[kUnroll];
+    IDX dst[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const IDX o = base + (IDX)(u * kThreads);
+        dst[u] = o;
+        if (o < (IDX)n_vec) {
+            // output run index -> (b, outer, inner); input run index swaps outer/inner
+            const IDX orun = o / (IDX)run;
+            const IDX r = o - orun * (IDX)run;
+            IDX irun;
+            if (TO_HEAD) {  // out runs ordered (b, p, s); in runs ordered (b, s, p)
+                const IDX bp = orun / (IDX)S_l;
+                const IDX s = orun - bp * (IDX)S_l;
+                const IDX b = bp / (IDX)P;
+                const IDX p = bp - b * (IDX)P;
+                irun = (b * (IDX)S_l + s) * (IDX)P + p;
+            } else {        // out runs ordered (b, s, p); in runs ordered (b, p, s)
+                const IDX bs = orun / (IDX)P;
+                const IDX p = orun - bs * (IDX)P;
+                const IDX b = bs / (IDX)S_l;
+                const IDX s = bs - b * (IDX)S_l;
+                irun = (b * (IDX)P + p) * (IDX)S_l + s;
+            }
+            val[u] = __builtin_nontemporal_load(in + (size_t)(irun * (IDX)run + r));
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+        if (dst[u] < (IDX)n_vec) __builtin_nontemporal_store(val[u], out + (size_t)dst[u]);
+}
+
+}  // namespace
+
+namespace sp {
+
+sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int64_t H, int64_t D,
+                          int32_t P, int32_t elem_bytes, bool to_head, hipStream_t st) {
+    const uint64_t h = (uint64_t)(H / P);
+    const uint64_t run = h * (uint64_t)D * (uint64_t)elem_bytes / 16;
+    const uint64_t n_vec = (uint64_t)B * (uint64_t)S_l * (uint64_t)P * run;
+    const uint64_t per_block = (uint64_t)kThreads * kUnroll;
+    const uint64_t blocks = (n_vec + per_block - 1) / per_block;
+    if (blocks == 0) return SP_OK;
+    if (blocks > 0x7fffffffull || run > 0xffffffffull) return SP_ERR_SHAPE;
+    if ((uint64_t)S_l > 0xffffffffull) return SP_ERR_SHAPE;
+    dim3 grid((unsigned)blocks), block(kThreads);
+    const bool small = n_vec + per_block < 0xffffffffull;  // every index, tail included, fits u32
+#define SP_RELAYOUT(TH, IDX)                                                                     \
+    hipLaunchKernelGGL((relayout_kernel<TH, IDX>), grid, block, 0, st, (const u32x4*)in,          \
+                       (u32x4*)out, n_vec, (uint32_t)run, (uint32_t)S_l, (uint32_t)P)
+    if (to_head) { if (small) SP_RELAYOUT(true, uint32_t); else SP_RELAYOUT(true, uint64_t); }
+    else         { if (small) SP_RELAYOUT(false, uint32_t); else SP_RELAYOUT(false, uint64_t); }
+#undef SP_RELAYOUT
+    return launch_status();
+}
+
+}  // namespace sp

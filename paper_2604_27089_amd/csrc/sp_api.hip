@@ -1,0 +1,187 @@
+// C-ABI entry points: argument validation on the host, then kernel launches on
+// the caller's stream.  Nothing here allocates, frees or synchronises.
+#include <math.h>
+
+#include "sp_common.h"
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+sp_status check_relayout(const void* in, void* out, int64_t B, int64_t S_l, int64_t H, int64_t D,
+                         int32_t P, int32_t elem_bytes) {
+    if (B < 0 || S_l < 0 || H < 0 || D < 0 || P <= 0) return SP_ERR_SHAPE;
+    if (H % P != 0) return SP_ERR_SHAPE;
+    if (elem_bytes != 2 && elem_bytes != 4) return SP_ERR_UNSUPPORTED;
+    if ((D * elem_bytes) % 16 != 0) return SP_ERR_UNSUPPORTED;
+    if (B == 0 || S_l == 0 || H == 0 || D == 0) return SP_OK;
+    if (!in || !out) return SP_ERR_NULL;
+    if (!sp::aligned16(in) || !sp::aligned16(out)) return SP_ERR_ALIGN;
+    return SP_OK;
+}
+
+sp_status check_attn_shape(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (B < 0 || S < 0 || Hq < 0 || Hkv < 0) return SP_ERR_SHAPE;
+    if (Hq == 0 || Hkv == 0) return (Hq == 0 && Hkv == 0) ? SP_OK : SP_ERR_SHAPE;
+    if (Hq % Hkv != 0) return SP_ERR_SHAPE;
+    if (D != 64 && D != 128) return SP_ERR_UNSUPPORTED;
+    if (S >= (int64_t)1 << 31 || B >= (int64_t)1 << 16 || B * S >= (int64_t)1 << 31) return SP_ERR_SHAPE;
+    return SP_OK;
+}
+
+inline float resolve_scale(float s, int32_t D) { return s > 0.f ? s : 1.0f / sqrtf((float)D); }
+
+// Workspace layout: [delta fp32 Hq*T (bwd only)] [row_lo int32 T] [row_hi int32 T] (varlen only),
+// each part rounded up to 256 bytes.
+size_t delta_bytes(int64_t T, int32_t Hq) { return align_up((size_t)T * (size_t)Hq * sizeof(float), 256); }
+size_t bounds_bytes(int64_t T) { return align_up((size_t)T * sizeof(int32_t), 256); }
+
+}  // namespace
+
+extern "C" {
+
+const char* sp_status_str(sp_status s) {
+    switch (s) {
+        case SP_OK: return "SP_OK";
+        case SP_ERR_NULL: return "SP_ERR_NULL: a required pointer is NULL";
+        case SP_ERR_SHAPE: return "SP_ERR_SHAPE: extents are negative, too large or do not divide";
+        case SP_ERR_UNSUPPORTED: return "SP_ERR_UNSUPPORTED: head dim or element size not supported";
+        case SP_ERR_WORKSPACE: return "SP_ERR_WORKSPACE: workspace too small";
+        case SP_ERR_ALIGN: return "SP_ERR_ALIGN: pointer not 16-byte aligned";
+        case SP_ERR_LAUNCH: return "SP_ERR_LAUNCH: HIP launch failed";
+    }
+    return "SP_ERR_?: unknown status";
+}
+
+int32_t sp_abi_version(void) { return 1; }
+
+sp_status sp_pack_seq_to_head(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
+                              int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream) {
+    sp_status st = check_relayout(in, out, B, S_l, H, D, P, elem_bytes);
+    if (st != SP_OK || B == 0 || S_l == 0 || H == 0 || D == 0) return st;
+    return sp::launch_relayout(in, out, B, S_l, H, D, P, elem_bytes, true, (hipStream_t)hip_stream);
+}
+
+sp_status sp_unpack_head_to_seq(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
+                                int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream) {
+    sp_status st = check_relayout(in, out, B, S_l, H, D, P, elem_bytes);
+    if (st != SP_OK || B == 0 || S_l == 0 || H == 0 || D == 0) return st;
+    return sp::launch_relayout(in, out, B, S_l, H, D, P, elem_bytes, false, (hipStream_t)hip_stream);
+}
+
+size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_t Hkv, int32_t D,
+                                   int32_t n_docs) {
+    if (n_docs < 0 || B <= 0) return 0;
+    const int64_t T = n_docs > 0 ? S_or_T : B * S_or_T;
+    if (check_attn_shape(n_docs > 0 ? 1 : B, S_or_T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
+    size_t n = delta_bytes(T, Hq);
+    if (n_docs > 0) n += 2 * bounds_bytes(T);
+    return n < 256 ? 256 : n;
+}
+
+size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                                          int32_t n_docs) {
+    if (n_docs < 0) return 0;
+    if (check_attn_shape(1, T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
+    const size_t n = 2 * bounds_bytes(T);
+    return n < 256 ? 256 : n;
+}
+
+sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
+                      int64_t S, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                      void* hip_stream) {
+    sp_status st = check_attn_shape(B, S, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (B == 0 || S == 0 || Hq == 0) return SP_OK;
+    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
+    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
+        !sp::aligned16(lse))
+        return SP_ERR_ALIGN;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                      const void* dO, void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
+                      int32_t D, float softmax_scale, void* hip_stream) {
+    sp_status st = check_attn_shape(B, S, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (B == 0 || S == 0 || Hq == 0) return SP_OK;
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0)) return SP_ERR_WORKSPACE;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
+    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
+    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)max_seqlen;
+    if (n_docs < 0) return SP_ERR_SHAPE;
+    sp_status st = check_attn_shape(1, T, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (T == 0 || Hq == 0) return SP_OK;
+    if (n_docs == 0) return SP_ERR_SHAPE;  // T > 0 rows must belong to some document
+    if (!q || !k || !v || !o || !lse || !cu_seqlens || !workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    int32_t* row_lo = (int32_t*)workspace;
+    int32_t* row_hi = (int32_t*)((char*)workspace + bounds_bytes(T));
+    st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
+    if (st != SP_OK) return st;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse; a.row_lo = row_lo; a.row_hi = row_hi;
+    a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_fwd(a, s);
+}
+
+sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o,
+                             const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)max_seqlen;
+    if (n_docs < 0) return SP_ERR_SHAPE;
+    sp_status st = check_attn_shape(1, T, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (T == 0 || Hq == 0) return SP_OK;
+    if (n_docs == 0) return SP_ERR_SHAPE;
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !cu_seqlens || !workspace)
+        return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    float* delta = (float*)workspace;
+    int32_t* row_lo = (int32_t*)((char*)workspace + delta_bytes(T, Hq));
+    int32_t* row_hi = (int32_t*)((char*)row_lo + bounds_bytes(T));
+    st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
+    if (st != SP_OK) return st;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
+    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
+    a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_bwd(a, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: it loads, it
+exports every symbol the header declares, and argument errors come back as
+status codes before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_27089_amd import binding as sp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sp_hotpath.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sp.lib()
+    names = declared_symbols()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in the header but not exported"
+    assert set(names) == set(sp.EXPORTS)
+    assert L.sp_abi_version() == 1
+
+
+def test_status_strings():
+    for code in range(7):
+        s = sp.status_str(code)
+        assert s.startswith("SP_")
+    assert "unknown" in sp.status_str(99)
+
+
+def A(n):  # a fake but aligned, non-null address; never dereferenced on error paths
+    return ctypes.c_void_p(0x1000 * n)
+
+
+def test_relayout_argument_errors():
+    L = sp.lib()
+    f = L.sp_pack_seq_to_head
+    assert f(A(1), A(2), 1, 8, 7, 64, 4, 2, None) == sp.SP_ERR_SHAPE        # H % P
+    assert f(A(1), A(2), 1, 8, 8, 64, 0, 2, None) == sp.SP_ERR_SHAPE        # P <= 0
+    assert f(A(1), A(2), -1, 8, 8, 64, 4, 2, None) == sp.SP_ERR_SHAPE
+    assert f(A(1), A(2), 1, 8, 8, 64, 4, 1, None) == sp.SP_ERR_UNSUPPORTED  # elem size
+    assert f(A(1), A(2), 1, 8, 8, 4, 4, 2, None) == sp.SP_ERR_UNSUPPORTED   # D*2 not x16
+    assert f(None, A(2), 1, 8, 8, 64, 4, 2, None) == sp.SP_ERR_NULL
+    assert f(ctypes.c_void_p(0x1008), A(2), 1, 8, 8, 64, 4, 2, None) == sp.SP_ERR_ALIGN
+    assert f(None, None, 1, 0, 8, 64, 4, 2, None) == sp.SP_OK               # empty
+    assert L.sp_unpack_head_to_seq(A(1), A(2), 1, 8, 6, 64, 4, 2, None) == sp.SP_ERR_SHAPE
+
+
+def test_attention_argument_errors():
+    L = sp.lib()
+    f = L.sp_attn_fwd
+    assert f(A(1), A(2), A(3), A(4), A(5), 1, 128, 4, 3, 128, 0.0, None) == sp.SP_ERR_SHAPE  # Hq % Hkv
+    assert f(A(1), A(2), A(3), A(4), A(5), 1, 128, 4, 1, 96, 0.0, None) == sp.SP_ERR_UNSUPPORTED
+    assert f(A(1), A(2), A(3), A(4), A(5), 1, 1 << 31, 4, 1, 128, 0.0, None) == sp.SP_ERR_SHAPE
+    assert f(None, A(2), A(3), A(4), A(5), 1, 128, 4, 1, 128, 0.0, None) == sp.SP_ERR_NULL
+    assert f(A(1), A(2), A(3), ctypes.c_void_p(0x4004), A(5), 1, 128, 4, 1, 128, 0.0, None) == sp.SP_ERR_ALIGN
+    assert f(None, None, None, None, None, 1, 0, 4, 1, 128, 0.0, None) == sp.SP_OK           # empty
+    need = sp.sp_attn_bwd_workspace_bytes(1, 1024, 4, 1, 128, 0)
+    assert need >= 4 * 1024 * 4
+    assert sp.sp_attn_bwd_workspace_bytes(1, 1024, 4, 3, 128, 0) == 0
+    assert sp.sp_attn_bwd_workspace_bytes(1, 1024, 4, 1, 128, 3) >= need + 2 * 4 * 1024
+    assert sp.sp_attn_varlen_fwd_workspace_bytes(1024, 4, 1, 128, 3) >= 2 * 4 * 1024
+    g = L.sp_attn_bwd
+    args = [A(i) for i in range(1, 11)]
+    assert g(*args, need - 1, 1, 1024, 4, 1, 128, 0.0, None) == sp.SP_ERR_WORKSPACE
+    assert g(*args[:9], None, need, 1, 1024, 4, 1, 128, 0.0, None) == sp.SP_ERR_NULL
+    vf = L.sp_attn_varlen_fwd
+    assert vf(A(1), A(2), A(3), A(4), A(5), A(6), 0, 0, 1024, 4, 1, 128, 0.0, A(7), 1 << 20, None) == sp.SP_ERR_SHAPE
+    assert vf(A(1), A(2), A(3), A(4), A(5), None, 2, 0, 1024, 4, 1, 128, 0.0, A(7), 1 << 20, None) == sp.SP_ERR_NULL
+    assert vf(A(1), A(2), A(3), A(4), A(5), A(6), 2, 0, 1024, 4, 1, 128, 0.0, A(7), 16, None) == sp.SP_ERR_WORKSPACE
+    vb = L.sp_attn_varlen_bwd
+    assert vb(*args[:9], A(11), 2, 0, 1024, 4, 1, 128, 0.0, A(12), 16, None) == sp.SP_ERR_WORKSPACE
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    monkeypatch.setattr(sp, "_lib", None)
+    monkeypatch.setattr(sp, "LIB_PATH", "/nonexistent/libsp_hotpath.so")
+    with pytest.raises(ImportError):
+        sp.lib()
