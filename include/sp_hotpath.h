@@ -133,6 +133,19 @@ sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o
                       size_t workspace_bytes, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
                       int32_t D, float softmax_scale, void* hip_stream);
 
+/* The same backward, one stage at a time.  `stages` is a bit mask of
+ * SP_BWD_STAGE_*; the stages of one backward must run in the order delta, then
+ * dkdv and dq (those two are independent of each other), all with the same
+ * arguments and workspace.  sp_attn_bwd(...) == stages SP_BWD_STAGE_ALL.
+ * Meant for per-stage timing and for callers that schedule the stages
+ * themselves. */
+enum { SP_BWD_STAGE_DELTA = 1, SP_BWD_STAGE_DKDV = 2, SP_BWD_STAGE_DQ = 4, SP_BWD_STAGE_ALL = 7 };
+sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const void* o,
+                             const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                             void* workspace, size_t workspace_bytes, int64_t B, int64_t S,
+                             int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             int32_t stages, void* hip_stream);
+
 /* ---------------------------------------------------------------------------
  * Packed variable-length documents (not in the paper; the block-diagonal form
  * of the same operator, as long-context training batches are usually packed).

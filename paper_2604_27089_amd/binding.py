@@ -21,7 +21,7 @@ SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_A
 
 EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
-    "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd",
+    "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
     "sp_attn_varlen_fwd", "sp_attn_varlen_bwd",
 )
 
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_varlen_fwd_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
     L.sp_attn_bwd.restype = c.c_int
     L.sp_attn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, f32, vp]
+    L.sp_attn_bwd_stages.restype = c.c_int
+    L.sp_attn_bwd_stages.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, f32, i32, vp]
     L.sp_attn_varlen_fwd.restype = c.c_int
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
@@ -149,6 +151,20 @@ def sp_attn_bwd(q, k, v, o, lse, do, softmax_scale: float = 0.0, dq=None, dk=Non
     _check(lib().sp_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq), _ptr(dk),
                              _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
                              float(softmax_scale), _stream(stream)), "sp_attn_bwd")
+    return dq, dk, dv
+
+
+SP_BWD_STAGE_DELTA, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
+
+
+def sp_attn_bwd_stages(q, k, v, o, lse, do, dq, dk, dv, workspace, stages: int, softmax_scale: float = 0.0,
+                       stream=None):
+    """One or more stages of the backward (bit mask of SP_BWD_STAGE_*); buffers are the caller's."""
+    B, S, Hq, D = q.shape
+    Hkv = k.shape[2]
+    _check(lib().sp_attn_bwd_stages(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
+                                    _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
+                                    float(softmax_scale), int(stages), _stream(stream)), "sp_attn_bwd_stages")
     return dq, dk, dv
 
 

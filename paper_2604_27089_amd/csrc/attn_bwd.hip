@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(BwdParams p) {
 
 template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
-    {
+    if (a.stages & SP_BWD_STAGE_DELTA) {
         const int64_t lanes = (int64_t)a.B * a.S * a.Hq * (D / 8);
         const int64_t blocks = (lanes + 255) / 256;
         if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
@@ -432,13 +432,13 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.row_lo = a.row_lo; p.row_hi = a.row_hi;
     p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
-    {
+    if (a.stages & SP_BWD_STAGE_DKDV) {
         p.n_tiles = (a.S + KV_BN - 1) / KV_BN;
         dim3 grid(p.n_tiles, a.Hkv, a.B);
         hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN>), grid, dim3(kThreads), 0, st, p);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
     }
-    {
+    if (a.stages & SP_BWD_STAGE_DQ) {
         p.n_tiles = (a.S + DQ_BM - 1) / DQ_BM;
         dim3 grid(p.n_tiles, a.Hq, a.B);
         hipLaunchKernelGGL((attn_bwd_dq_kernel<D, VARLEN>), grid, dim3(kThreads), 0, st, p);

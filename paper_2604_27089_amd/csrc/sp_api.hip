@@ -108,8 +108,18 @@ sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o
                       const void* dO, void* dq, void* dk, void* dv, void* workspace,
                       size_t workspace_bytes, int64_t B, int64_t S, int32_t Hq, int32_t Hkv,
                       int32_t D, float softmax_scale, void* hip_stream) {
+    return sp_attn_bwd_stages(q, k, v, o, lse, dO, dq, dk, dv, workspace, workspace_bytes, B, S, Hq,
+                              Hkv, D, softmax_scale, SP_BWD_STAGE_ALL, hip_stream);
+}
+
+sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const void* o,
+                             const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                             void* workspace, size_t workspace_bytes, int64_t B, int64_t S,
+                             int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             int32_t stages, void* hip_stream) {
     sp_status st = check_attn_shape(B, S, Hq, Hkv, D);
     if (st != SP_OK) return st;
+    if (stages <= 0 || (stages & ~SP_BWD_STAGE_ALL) != 0) return SP_ERR_SHAPE;
     if (B == 0 || S == 0 || Hq == 0) return SP_OK;
     if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
     const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
@@ -121,6 +131,7 @@ sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
+    a.stages = stages;
     return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
 }
 
@@ -181,6 +192,7 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
+    a.stages = SP_BWD_STAGE_ALL;
     return sp::launch_attn_bwd(a, s);
 }
 

@@ -26,6 +26,7 @@ struct AttnArgs {
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
     int32_t B, S, Hq, Hkv, D;
     float scale;            // softmax scale (already defaulted)
+    int32_t stages;         // bwd: bit mask of SP_BWD_STAGE_*
 };
 
 sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int64_t H, int64_t D,
