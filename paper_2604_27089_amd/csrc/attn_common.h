@@ -77,3 +77,92 @@ __device__ __forceinline__ void transpose4x8(const u32x4 (&row)[4], u32x2 (&col)
 }
 
 }  // namespace sp
+
+// ---------------------------------------------------------------------------
+// Unpadded, XOR-swizzled LDS tiles filled by direct global->LDS loads.
+//
+// A tile holds ROWS rows of D bf16 (D*2 bytes, CH = D/8 chunks of 16 bytes).
+// Chunk c of row r is stored at chunk position c ^ swz<D>(r).  The swizzle is
+// chosen so that both access patterns of the attention kernels are free of
+// bank conflicts (64 banks x 4 bytes):
+//   - row-major operand reads (ds_read_b128): 16 consecutive rows, same chunk;
+//   - transposing reads (ds_read_b64_tr_b16): 4 consecutive rows (row % 4 = 0..3)
+//     x 4 consecutive chunks per half-wave.
+// ---------------------------------------------------------------------------
+namespace sp {
+
+template <int D>
+__device__ __forceinline__ int swz(int row);
+template <>
+__device__ __forceinline__ int swz<128>(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+template <>
+__device__ __forceinline__ int swz<64>(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
+#define SP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define SP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// One wave copies 1024 contiguous LDS bytes: lane l supplies the 16 global bytes
+// that land at lds_base + 16*l (lds_base must be wave-uniform).
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_base) {
+    __builtin_amdgcn_global_load_lds(SP_GPTR(gsrc), SP_LPTR(lds_base), 16, 0, 0);
+}
+
+// All of this wave's outstanding global loads (register and LDS destinations) have landed.
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// Transposing LDS read: within each 16-lane block, lane i receives element i%4... see
+// tile_dma_rows/tr_operand below for how the kernels use it.
+__device__ __forceinline__ s16x4 lds_read_tr16(const void* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+}
+
+// Per-lane description of the DMA loads that fill one ROWS x D tile with 256 threads.
+// Instruction i (0 .. ROWS*CH/64-1) covers 64/CH rows; wave w issues i = w, w+4, ...
+template <int D, int ROWS>
+struct TileDma {
+    static constexpr int CH = D / 8;
+    static constexpr int RPI = 64 / CH;             // rows per instruction
+    static constexpr int N_INSTR = ROWS * CH / 64;  // per tile, all waves
+    static constexpr int PER_WAVE = N_INSTR / 4;
+    int row[PER_WAVE];    // row inside the tile this lane fetches for its k-th instruction
+    int chunk8[PER_WAVE]; // element offset (chunk * 8) inside the global row
+    __device__ __forceinline__ void init(int wave, int lane) {
+#pragma unroll
+        for (int k = 0; k < PER_WAVE; ++k) {
+            const int i = wave + 4 * k;
+            row[k] = RPI * i + lane / CH;
+            chunk8[k] = ((lane % CH) ^ swz<D>(row[k])) * 8;
+        }
+    }
+    // rows first_row + row[k], clamped to last_valid_row, of a [*, row_stride] bf16 matrix -> tile at lds
+    __device__ __forceinline__ void issue(const __bf16* gbase, size_t row_stride, int first_row,
+                                          int last_valid_row, __bf16* lds, int wave) const {
+#pragma unroll
+        for (int k = 0; k < PER_WAVE; ++k) {
+            int r = first_row + row[k];
+            r = r < last_valid_row ? r : last_valid_row;
+            dma16(gbase + (size_t)r * row_stride + chunk8[k], lds + (wave + 4 * k) * 512);
+        }
+    }
+};
+
+// Byte offset, inside a swizzled tile, of the 16-byte row-major operand chunk (row, chunk).
+template <int D>
+__device__ __forceinline__ int tile_off_b128(int row, int chunk) {
+    return row * (D * 2) + ((chunk ^ swz<D>(row)) * 16);
+}
+
+// Byte offset this lane passes to the transposing read so that, together with the other
+// lanes of its 16-lane block, it receives rows {row0 .. row0+3} of column (col0 + i) where i
+// is its index in the block: lane i supplies row row0 + i/4, columns col0 + 4*(i%4) .. +3.
+template <int D>
+__device__ __forceinline__ int tile_off_tr(int row0, int col0, int i16) {
+    const int row = row0 + (i16 >> 2);
+    const int col = col0 + 4 * (i16 & 3);
+    return row * (D * 2) + (((col >> 3) ^ swz<D>(row)) * 16) + (col & 7) * 2;
+}
+
+}  // namespace sp

@@ -3,16 +3,17 @@
 // on its heads over the whole context; Section 3.1 challenge 3: causal mask).
 //
 // One workgroup = 4 waves = 128 query rows of one query head; each wave owns 32
-// rows.  Keys/values stream through LDS in tiles of 64.  Per tile and wave:
+// rows; two workgroups share a CU so one's MFMA phase overlaps the other's
+// softmax.  Keys/values stream through LDS in tiles of 64, double-buffered and
+// filled by direct global->LDS loads into an unpadded XOR-swizzled layout (no
+// staging registers, one barrier per tile).  Per tile and wave:
 //   S^T[key, query] = K_tile . Q^T          (MFMA; K from LDS as A, Q resident as B)
 //   online softmax in fp32: with queries on the lane axis of the accumulator,
 //     a row's maximum and sum are register-local plus one swap between the two
-//     wave halves
-//   O^T[d, query] += V_tile^T . P^T         (MFMA; V^T from LDS as A, the S^T
-//     accumulator registers, rounded to bf16, are already a valid B operand)
-// V is transposed once, on its way into LDS (4x8 register transpose, 8-byte
-// LDS stores in operand order).  The next tile's global loads are issued before
-// the current tile's arithmetic and parked in registers.
+//     wave halves; O is rescaled only when some row's maximum moves
+//   O^T[d, query] += V_tile^T . P^T         (MFMA; V^T read from the row-major V
+//     tile with transposing LDS reads; the S^T accumulator registers, rounded
+//     to bf16, are already a valid B operand)
 #include "attn_common.h"
 #include "sp_common.h"
 
@@ -24,14 +25,6 @@ constexpr int kThreads = 256;
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 64;   // keys per tile
 
-template <int D>
-struct FwdSmem {
-    static constexpr int LDK = D + 8;   // K tile row stride (bf16), padded
-    static constexpr int LDV = BN + 8;  // V^T tile row stride (bf16), padded
-    __bf16 k[BN * LDK];
-    __bf16 vt[D * LDV];
-};
-
 struct FwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v;
     __bf16* o; float* lse;
@@ -41,12 +34,11 @@ struct FwdParams {
 };
 
 template <int D, bool VARLEN>
-__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
-    constexpr int KCH = D / 8;                       // 16-byte chunks per row
-    constexpr int K_LOADS = BN * KCH / kThreads;     // K chunks per thread per tile
-    constexpr int V_TASKS = (BN / 4) * KCH;          // 4-key x 8-dim transposing tasks
-    constexpr int LDK = FwdSmem<D>::LDK, LDV = FwdSmem<D>::LDV;
-    __shared__ FwdSmem<D> sm;
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(FwdParams p) {
+    constexpr int TILE = BN * D;  // elements per K or V tile
+    // two K and two V tiles (double buffer), unpadded and swizzled, filled by direct global->LDS loads
+    __shared__ __attribute__((aligned(1024))) __bf16 ks[2 * TILE];
+    __shared__ __attribute__((aligned(1024))) __bf16 vs[2 * TILE];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     // heaviest (latest) query tiles first
@@ -83,6 +75,20 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     const int last_row = (i0 + BM - 1 < S ? i0 + BM - 1 : S - 1);
     const int jt_end = last_row / BN + 1;  // exclusive
 
+    // LDS byte offsets of this lane's operand reads, tile-invariant
+    int koff[D / 16];  // K row-major operand: row 32*nb + lo (nb adds a constant), chunk 2*kk + hi
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) koff[kk] = tile_off_b128<D>(lo, 2 * kk + hi);
+    int voff[2][D / 32];  // V^T operand via transposing reads: rows 16*c + 8*half + 4*hi + (0..3), cols 32*db + 16*(lo/16) + (lo%16)
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+            voff[half][db] = tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
+
+    TileDma<D, BN> dma;
+    dma.init(wave, lane);
+
     f32x16 oacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
@@ -91,50 +97,18 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     float m_run = -INFINITY;  // running maximum, in log2 units (score * scale * log2 e)
     float l_run = 0.f;        // this lane's share of the running sum
 
-    // ---- global -> register staging of one K/V tile ----
-    u32x4 kst[K_LOADS];
-    u32x4 vst[4];
-    const int v_kg = tid / KCH, v_c = tid % KCH;  // transposing task of this thread
-    auto load_tile = [&](int jt) {
-        const int j0 = jt * BN;
-#pragma unroll
-        for (int u = 0; u < K_LOADS; ++u) {
-            const int c = tid + u * kThreads;
-            int row = j0 + c / KCH;
-            row = row < S ? row : S - 1;
-            kst[u] = *reinterpret_cast<const u32x4*>(kb + (size_t)row * kv_row_stride + 8 * (c % KCH));
-        }
-        if (tid < V_TASKS) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int row = j0 + 4 * v_kg + e;
-                row = row < S ? row : S - 1;
-                vst[e] = *reinterpret_cast<const u32x4*>(vb + (size_t)row * kv_row_stride + 8 * v_c);
-            }
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int u = 0; u < K_LOADS; ++u) {
-            const int c = tid + u * kThreads;
-            *reinterpret_cast<u32x4*>(&sm.k[(c / KCH) * LDK + 8 * (c % KCH)]) = kst[u];
-        }
-        if (tid < V_TASKS) {
-            u32x2 col[8];
-            transpose4x8(vst, col);
-            const int pos = operand_pos4(v_kg);
-#pragma unroll
-            for (int dd = 0; dd < 8; ++dd)
-                *reinterpret_cast<u32x2*>(&sm.vt[(8 * v_c + dd) * LDV + pos]) = col[dd];
-        }
-    };
-
-    if (jt_begin < jt_end) load_tile(jt_begin);
+    dma.issue(kb, kv_row_stride, jt_begin * BN, S - 1, ks, wave);
+    dma.issue(vb, kv_row_stride, jt_begin * BN, S - 1, vs, wave);
     for (int jt = jt_begin; jt < jt_end; ++jt) {
-        __syncthreads();  // everyone finished reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (jt + 1 < jt_end) load_tile(jt + 1);
+        const int buf = (jt - jt_begin) & 1;
+        wait_vmem();      // this wave's part of tile jt is in LDS
+        __syncthreads();  // ... and everybody else's; everybody is also done reading tile jt-1
+        if (jt + 1 < jt_end) {
+            dma.issue(kb, kv_row_stride, (jt + 1) * BN, S - 1, ks + (buf ^ 1) * TILE, wave);
+            dma.issue(vb, kv_row_stride, (jt + 1) * BN, S - 1, vs + (buf ^ 1) * TILE, wave);
+        }
+        const char* kt = reinterpret_cast<const char*>(ks + buf * TILE);
+        const char* vt = reinterpret_cast<const char*>(vs + buf * TILE);
 
         const int j0 = jt * BN;
         // does this wave have any visible key in the tile?
@@ -150,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
             for (int r = 0; r < 16; ++r) sacc[nb][r] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < D / 16; ++kk) {
-                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.k[(32 * nb + lo) * LDK + 16 * kk + 8 * hi]));
+                const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kt + koff[kk] + nb * (32 * D * 2)));
                 sacc[nb] = mfma32(a, qreg[kk], sacc[nb]);
             }
         }
@@ -174,10 +148,22 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[nb][r]);
-        mx = fmaxf(mx, xhalf(mx));
-        const float m_new = fmaxf(m_run, mx * p.scale_log2);
-        const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;  // fully masked so far
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_sub);
+        mx = fmaxf(mx, xhalf(mx)) * p.scale_log2;
+        // O is rescaled only on tiles where some row of the wave raises its maximum (a few
+        // percent of the tiles at long sequence length).  The reference stays the exact row
+        // maximum, so the dominant weight of a peaked row is exactly 1 before bf16 rounding.
+        if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+            const float m_new = fmaxf(m_run, mx);
+            const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;  // fully masked so far
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_sub);
+            l_run *= alpha;
+            m_run = m_new;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        }
+        const float m_sub = (m_run == -INFINITY) ? 0.f : m_run;
         float psum = 0.f;
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
@@ -187,27 +173,19 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
                 sacc[nb][r] = e;
                 psum += e;
             }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        l_run += psum;
+        // ---- O^T += V^T . P^T, 16 keys per step ----
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+        for (int c = 0; c < BN / 16; ++c) {
+            const bf16x8 pb = acc_to_operand(sacc[c / 2], 8 * (c % 2));
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-        // ---- O^T += V^T . P^T ----
-        bf16x8 pb[2][2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) pb[nb][c] = acc_to_operand(sacc[nb], 8 * c);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.vt[(32 * db + lo) * LDV + 16 * (2 * nb + c) + 8 * hi]));
-                    oacc[db] = mfma32(a, pb[nb][c], oacc[db]);
-                }
+            for (int db = 0; db < D / 32; ++db) {
+                const s16x4 v0 = lds_read_tr16(vt + voff[0][db] + c * (16 * D * 2));
+                const s16x4 v1 = lds_read_tr16(vt + voff[1][db] + c * (16 * D * 2));
+                const s16x8 a8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                oacc[db] = mfma32(__builtin_bit_cast(bf16x8, a8), pb, oacc[db]);
+            }
+        }
     }
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log) ----
