@@ -15,7 +15,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsp_hotpath.so")
+# SP_HOTPATH_LIB points at another build of the same library (e.g. an experimental variant).
+LIB_PATH = os.environ.get("SP_HOTPATH_LIB") or os.path.join(_HERE, "libsp_hotpath.so")
 
 SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_ALIGN, SP_ERR_LAUNCH = range(7)
 

@@ -13,6 +13,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace sp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -23,6 +26,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// compile-time loop: f(std::integral_constant<int, I>{}) for I in [B, E)
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(static_cast<F&&>(f));
+    }
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -61,8 +73,15 @@ __device__ __forceinline__ int operand_pos4(int group4) {  // group4 = row/4
     return 16 * blk + 4 * pb;
 }
 
-// exchange with the other 32-lane half of the wave
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
+// value held by the same lane of the other 32-lane half of the wave (v_permlane32_swap)
+__device__ __forceinline__ float xhalf(float x) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    // swaps the upper half of the first operand with the lower half of the second
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    // r[0]: lanes 0-31 keep x, lanes 32-63 receive the lower half; r[1]: lanes 0-31 receive the upper half
+    const uint32_t other = (__lane_id() < 32) ? r[1] : r[0];
+    return __builtin_bit_cast(float, other);
+}
 
 // Transpose a 4 (rows) x 8 (cols) bf16 block held as four 16-byte row vectors
 // into eight 8-byte column vectors (4 rows each).
@@ -119,32 +138,85 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
 }
 
-// Per-lane description of the DMA loads that fill one ROWS x D tile with 256 threads.
-// Instruction i (0 .. ROWS*CH/64-1) covers 64/CH rows; wave w issues i = w, w+4, ...
-template <int D, int ROWS>
+// ---------------------------------------------------------------------------
+// Asynchronous LDS operand reads with explicit waits.
+//
+// The compiler waits for ALL outstanding LDS reads before the first use of any
+// of them; a software pipeline that keeps several operand reads in flight needs
+// partial waits.  These helpers issue the read as opaque assembly (the compiler
+// then tracks nothing) and lds_wait<N>(x) blocks until at most N younger LDS
+// reads are outstanding, tying x to the wait so no use of x can be placed before
+// it.  LDS reads of a wave complete in order, which makes the count exact.
+// Rule: every value produced by lds_async_* must pass through lds_wait before
+// it is used in any way, a register copy included: so such values never cross a
+// control-flow join and are never packed into wider vectors before the wait.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(p);
+}
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_async_b128(uint32_t addr) {
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_async_tr16(uint32_t addr) {
+    u32x2 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4& x) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x2& x, u32x2& y) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
+}
+
+// Per-lane description of the DMA loads that fill one ROWS x D tile with NW waves.
+// (NW waves).  Instruction i (0 .. ROWS*CH/64-1) covers 64/CH rows; wave w issues i = w, w+NW, ...
+// `wave` must be wave-uniform in the scalar sense (readfirstlane) so that LDS
+// destinations are scalar.  Global addresses are a scalar tile base plus a 32-bit
+// per-lane byte offset (rows of a tile span far less than 4 GiB).
+template <int D, int ROWS, int NW = 4>
 struct TileDma {
     static constexpr int CH = D / 8;
     static constexpr int RPI = 64 / CH;             // rows per instruction
     static constexpr int N_INSTR = ROWS * CH / 64;  // per tile, all waves
-    static constexpr int PER_WAVE = N_INSTR / 4;
-    int row[PER_WAVE];    // row inside the tile this lane fetches for its k-th instruction
-    int chunk8[PER_WAVE]; // element offset (chunk * 8) inside the global row
-    __device__ __forceinline__ void init(int wave, int lane) {
+    static constexpr int PER_WAVE = N_INSTR / NW;
+    static_assert(N_INSTR % NW == 0, "tile must split evenly over the waves");
+    int row[PER_WAVE];      // row inside the tile this lane fetches for its k-th instruction
+    uint32_t off[PER_WAVE]; // byte offset from the tile's first row, for a full (unclamped) tile
+    uint32_t chunk_b;       // byte offset of the lane's chunk inside a row (same for all k: RPI*4 is a multiple of 16)
+    uint32_t stride_b;      // global row stride in bytes
+    __device__ __forceinline__ void init(int wave, int lane, size_t row_stride_elems) {
+        stride_b = (uint32_t)(row_stride_elems * 2);
 #pragma unroll
         for (int k = 0; k < PER_WAVE; ++k) {
-            const int i = wave + 4 * k;
+            const int i = wave + NW * k;
             row[k] = RPI * i + lane / CH;
-            chunk8[k] = ((lane % CH) ^ swz<D>(row[k])) * 8;
+            const uint32_t cb = (uint32_t)(((lane % CH) ^ swz<D>(row[k])) * 16);
+            off[k] = (uint32_t)row[k] * stride_b + cb;
+            chunk_b = cb;
         }
     }
-    // rows first_row + row[k], clamped to last_valid_row, of a [*, row_stride] bf16 matrix -> tile at lds
-    __device__ __forceinline__ void issue(const __bf16* gbase, size_t row_stride, int first_row,
-                                          int last_valid_row, __bf16* lds, int wave) const {
+    // rows first_row .. first_row+ROWS-1 of the matrix at gbase -> tile at lds; rows past
+    // last_valid_row re-read last_valid_row (their values are never used unmasked).
+    __device__ __forceinline__ void issue(const __bf16* gbase, int first_row, int last_valid_row,
+                                          __bf16* lds, int wave) const {
+        const char* tile = reinterpret_cast<const char*>(gbase) + (size_t)first_row * stride_b;  // scalar
+        if (first_row + ROWS - 1 <= last_valid_row) {
 #pragma unroll
-        for (int k = 0; k < PER_WAVE; ++k) {
-            int r = first_row + row[k];
-            r = r < last_valid_row ? r : last_valid_row;
-            dma16(gbase + (size_t)r * row_stride + chunk8[k], lds + (wave + 4 * k) * 512);
+            for (int k = 0; k < PER_WAVE; ++k) dma16(tile + off[k], lds + (wave + NW * k) * 512);
+        } else {
+            const int lim = last_valid_row - first_row;
+#pragma unroll
+            for (int k = 0; k < PER_WAVE; ++k) {
+                const int r = row[k] < lim ? row[k] : lim;
+                dma16(tile + ((uint32_t)r * stride_b + (off[k] - (uint32_t)row[k] * stride_b)), lds + (wave + NW * k) * 512);
+            }
         }
     }
 };
