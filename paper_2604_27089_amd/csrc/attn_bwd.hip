@@ -259,7 +259,7 @@ struct DqSmem {
 };
 
 template <int D, bool VARLEN>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(BwdParams p) {
     constexpr int KCH = D / 8;
     constexpr int V_LOADS = DQ_BN * KCH / kThreads;
     constexpr int TASKS = (DQ_BN / 4) * KCH;

@@ -187,37 +187,32 @@ struct TileDma {
     static constexpr int N_INSTR = ROWS * CH / 64;  // per tile, all waves
     static constexpr int PER_WAVE = N_INSTR / NW;
     static_assert(N_INSTR % NW == 0, "tile must split evenly over the waves");
-    int row[PER_WAVE];      // row inside the tile this lane fetches for its k-th instruction
-    uint32_t off[PER_WAVE]; // byte offset from the tile's first row, for a full (unclamped) tile
-    uint32_t chunk_b;       // byte offset of the lane's chunk inside a row (same for all k: RPI*4 is a multiple of 16)
-    uint32_t stride_b;      // global row stride in bytes
+    int row[PER_WAVE];          // row inside the tile this lane fetches for its k-th instruction
+    uint32_t chunk_b[PER_WAVE]; // byte offset of the (swizzled) chunk this lane fetches inside that row
+    uint32_t stride_b;          // global row stride in bytes
     __device__ __forceinline__ void init(int wave, int lane, size_t row_stride_elems) {
         stride_b = (uint32_t)(row_stride_elems * 2);
 #pragma unroll
         for (int k = 0; k < PER_WAVE; ++k) {
             const int i = wave + NW * k;
             row[k] = RPI * i + lane / CH;
-            const uint32_t cb = (uint32_t)(((lane % CH) ^ swz<D>(row[k])) * 16);
-            off[k] = (uint32_t)row[k] * stride_b + cb;
-            chunk_b = cb;
+            chunk_b[k] = (uint32_t)(((lane % CH) ^ swz<D>(row[k])) * 16);
         }
     }
-    // rows first_row .. first_row+ROWS-1 of the matrix at gbase -> tile at lds; rows past
-    // last_valid_row re-read last_valid_row (their values are never used unmasked).
+    // The K-th of this wave's PER_WAVE loads for the tile whose first row is first_row; rows
+    // past last_valid_row re-read last_valid_row (their values are never used unmasked).
+    // Branch-free, so it can sit inside software-pipelined code.
+    template <int K>
+    __device__ __forceinline__ void issue_one(const __bf16* gbase, int first_row, int last_valid_row,
+                                              __bf16* lds, int wave) const {
+        const char* tile = reinterpret_cast<const char*>(gbase) + (size_t)first_row * stride_b;  // scalar
+        const int lim = last_valid_row - first_row;
+        const int r = row[K] < lim ? row[K] : lim;
+        dma16(tile + ((uint32_t)r * stride_b + chunk_b[K]), lds + (wave + NW * K) * 512);
+    }
     __device__ __forceinline__ void issue(const __bf16* gbase, int first_row, int last_valid_row,
                                           __bf16* lds, int wave) const {
-        const char* tile = reinterpret_cast<const char*>(gbase) + (size_t)first_row * stride_b;  // scalar
-        if (first_row + ROWS - 1 <= last_valid_row) {
-#pragma unroll
-            for (int k = 0; k < PER_WAVE; ++k) dma16(tile + off[k], lds + (wave + NW * k) * 512);
-        } else {
-            const int lim = last_valid_row - first_row;
-#pragma unroll
-            for (int k = 0; k < PER_WAVE; ++k) {
-                const int r = row[k] < lim ? row[k] : lim;
-                dma16(tile + ((uint32_t)r * stride_b + (off[k] - (uint32_t)row[k] * stride_b)), lds + (wave + NW * k) * 512);
-            }
-        }
+        static_for<0, PER_WAVE>([&](auto K) { issue_one<decltype(K)::value>(gbase, first_row, last_valid_row, lds, wave); });
     }
 };
 
