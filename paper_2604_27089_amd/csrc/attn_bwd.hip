@@ -28,8 +28,10 @@ constexpr int kThreads = 256;
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o,
                                                    const __bf16* __restrict__ dO,
-                                                   float* __restrict__ delta, int32_t B, int32_t S,
-                                                   int32_t Hq) {
+                                                   const float* __restrict__ lse,
+                                                   float* __restrict__ delta, float* __restrict__ lsn,
+                                                   float* __restrict__ dn, int32_t B, int32_t S,
+                                                   int32_t S_pad, int32_t Hq, float inv_scale) {
     constexpr int LPV = D / 8;  // lanes per (row, head) vector, 16 bytes each
     const int64_t n_vec = (int64_t)B * S * Hq;
     const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;
@@ -49,7 +51,23 @@ __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o
         const int64_t b = bi / S;
         const int32_t i = (int32_t)(bi - b * S);
         delta[(b * Hq + h) * S + i] = acc;
+        // the per-row accumulator seeds of the dK/dV kernel
+        lsn[(b * Hq + h) * S_pad + i] = -lse[(b * Hq + h) * S + i] * inv_scale;
+        dn[(b * Hq + h) * S_pad + i] = -acc;
     }
+}
+
+// zero the padding rows [S, S_pad) of the per-row scalars (they are fetched, never used unmasked)
+__global__ __launch_bounds__(256) void aux_pad_kernel(float* __restrict__ lsn, float* __restrict__ dn,
+                                                     int32_t BH, int32_t S, int32_t S_pad) {
+    const int32_t pad = S_pad - S;
+    const int64_t n = (int64_t)BH * pad;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n) return;
+    const int64_t bh = t / pad;
+    const int32_t i = S + (int32_t)(t - bh * pad);
+    lsn[bh * S_pad + i] = 0.f;
+    dn[bh * S_pad + i] = 0.f;
 }
 
 struct BwdParams {
@@ -60,190 +78,6 @@ struct BwdParams {
     int32_t S, Hq, Hkv, G, n_tiles;
     float scale, scale_log2;
 };
-
-// ------------------------------------------------------------------ dK, dV
-constexpr int KV_BN = 128;  // keys per workgroup (32 per wave)
-constexpr int KV_BM = 64;   // query rows per streamed tile
-
-template <int D>
-struct DkdvSmem {
-    static constexpr int LDR = D + 8;      // row-major tiles [KV_BM][LDR]
-    static constexpr int LDT = KV_BM + 8;  // transposed tiles [D][LDT]
-    __bf16 q[KV_BM * LDR];
-    __bf16 dO[KV_BM * LDR];
-    __bf16 qt[D * LDT];
-    __bf16 dOt[D * LDT];
-    float lse2[KV_BM];   // LSE * log2(e)
-    float delta[KV_BM];
-};
-
-template <int D, bool VARLEN>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(BwdParams p) {
-    constexpr int KCH = D / 8;
-    constexpr int TASKS = (KV_BM / 4) * KCH;  // 4-row x 8-col transposing tasks per tile
-    constexpr int LDR = DkdvSmem<D>::LDR, LDT = DkdvSmem<D>::LDT;
-    __shared__ DkdvSmem<D> sm;
-
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-    const int jt = blockIdx.x;  // earliest key tiles (most work) first
-    const int g = blockIdx.y, b = blockIdx.z;
-    const int S = p.S;
-    const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
-    const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
-    const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
-
-    const int j0 = jt * KV_BN;
-    const int wkey0 = j0 + 32 * wave;
-    const int key = wkey0 + lo;
-    const int key_c = key < S ? key : S - 1;
-
-    // resident B operands: K^T and V^T columns of this lane's key
-    bf16x8 kreg[D / 16], vreg[D / 16];
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-        kreg[kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
-        vreg[kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
-    }
-    int key_hi = S;       // one past the last query row that may see this key
-    int wave_hi_min = S, wave_hi_max = S;  // over the wave's keys
-    int wg_hi_max = S;
-    if (VARLEN) {
-        key_hi = p.row_hi[key_c];
-        wave_hi_min = p.row_hi[(wkey0 < S ? wkey0 : S - 1)];
-        wave_hi_max = p.row_hi[(wkey0 + 31 < S ? wkey0 + 31 : S - 1)];
-        wg_hi_max = p.row_hi[(j0 + KV_BN - 1 < S ? j0 + KV_BN - 1 : S - 1)];
-    }
-    const int wave_key_min = wkey0, wave_key_max = wkey0 + 31;
-
-    f32x16 dkacc[D / 32], dvacc[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
-
-    const int it_begin = j0 / KV_BM;
-    const int it_end = (wg_hi_max + KV_BM - 1) / KV_BM;  // exclusive
-    const int n_it = it_end - it_begin;
-    const int total = n_it * p.G;  // (head in group, query tile) pairs
-
-    u32x4 qst[4], dost[4];
-    float lse_st = 0.f, delta_st = 0.f;
-    const int t_kg = tid / KCH, t_c = tid % KCH;
-    auto load_tile = [&](int step) {
-        const int a = g * p.G + step / n_it;
-        const int i0 = (it_begin + step % n_it) * KV_BM;
-        const __bf16* qb = p.q + ((size_t)b * S * p.Hq + a) * D;
-        const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + a) * D;
-        if (tid < TASKS) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int row = i0 + 4 * t_kg + e;
-                row = row < S ? row : S - 1;
-                qst[e] = *reinterpret_cast<const u32x4*>(qb + (size_t)row * q_row_stride + 8 * t_c);
-                dost[e] = *reinterpret_cast<const u32x4*>(dob + (size_t)row * q_row_stride + 8 * t_c);
-            }
-        }
-        if (tid < KV_BM) {
-            int row = i0 + tid;
-            row = row < S ? row : S - 1;
-            lse_st = p.lse[((size_t)b * p.Hq + a) * S + row] * kLog2e;
-            delta_st = p.delta[((size_t)b * p.Hq + a) * S + row];
-        }
-    };
-    auto store_tile = [&]() {
-        if (tid < TASKS) {
-            u32x2 col[8];
-            const int pos = operand_pos4(t_kg);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                *reinterpret_cast<u32x4*>(&sm.q[(4 * t_kg + e) * LDR + 8 * t_c]) = qst[e];
-                *reinterpret_cast<u32x4*>(&sm.dO[(4 * t_kg + e) * LDR + 8 * t_c]) = dost[e];
-            }
-            transpose4x8(qst, col);
-#pragma unroll
-            for (int dd = 0; dd < 8; ++dd) *reinterpret_cast<u32x2*>(&sm.qt[(8 * t_c + dd) * LDT + pos]) = col[dd];
-            transpose4x8(dost, col);
-#pragma unroll
-            for (int dd = 0; dd < 8; ++dd) *reinterpret_cast<u32x2*>(&sm.dOt[(8 * t_c + dd) * LDT + pos]) = col[dd];
-        }
-        if (tid < KV_BM) { sm.lse2[tid] = lse_st; sm.delta[tid] = delta_st; }
-    };
-
-    if (total > 0) load_tile(0);
-    for (int step = 0; step < total; ++step) {
-        __syncthreads();
-        store_tile();
-        __syncthreads();
-        if (step + 1 < total) load_tile(step + 1);
-
-        const int i0 = (it_begin + step % n_it) * KV_BM;
-        // per 32-row block of the tile
-#pragma unroll
-        for (int mb = 0; mb < KV_BM / 32; ++mb) {
-            const int q0 = i0 + 32 * mb;  // rows q0 .. q0+31
-            bool active = q0 + 31 >= wave_key_min && q0 < S;
-            if (VARLEN) active = active && q0 < wave_hi_max;
-            if (!active) continue;
-            // ---- S = Q.K^T and dP = dO.V^T (rows = queries in registers, column = this lane's key) ----
-            f32x16 sacc, pacc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
-#pragma unroll
-            for (int kk = 0; kk < D / 16; ++kk) {
-                const bf16x8 aq = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.q[(32 * mb + lo) * LDR + 16 * kk + 8 * hi]));
-                sacc = mfma32(aq, kreg[kk], sacc);
-                const bf16x8 ad = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.dO[(32 * mb + lo) * LDR + 16 * kk + 8 * hi]));
-                pacc = mfma32(ad, vreg[kk], pacc);
-            }
-            bool need_mask = (q0 < wave_key_max) || (q0 + 31 >= S);
-            if (VARLEN) need_mask = need_mask || (q0 + 31 >= wave_hi_min);
-            // ---- P and dS ----
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse2[32 * mb + 8 * gq + 4 * hi]);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[32 * mb + 8 * gq + 4 * hi]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * gq + e;
-                    float pij = __builtin_amdgcn_exp2f(sacc[r] * p.scale_log2 - l4[e]);
-                    if (need_mask) {
-                        const int qrow = q0 + 8 * gq + 4 * hi + e;
-                        const bool vis = qrow >= key && qrow < key_hi;
-                        pij = vis ? pij : 0.f;
-                    }
-                    sacc[r] = pij;
-                    pacc[r] = pij * (pacc[r] - d4[e]);
-                }
-            }
-            // ---- dV += P^T.dO, dK += dS^T.Q ----
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const bf16x8 pa = acc_to_operand(sacc, 8 * c);
-                const bf16x8 dsa = acc_to_operand(pacc, 8 * c);
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db) {
-                    const bf16x8 bd = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.dOt[(32 * db + lo) * LDT + 16 * (2 * mb + c) + 8 * hi]));
-                    dvacc[db] = mfma32(pa, bd, dvacc[db]);
-                    const bf16x8 bq = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm.qt[(32 * db + lo) * LDT + 16 * (2 * mb + c) + 8 * hi]));
-                    dkacc[db] = mfma32(dsa, bq, dkacc[db]);
-                }
-            }
-        }
-    }
-
-    // ---- write dK (scaled) and dV: accumulator rows = keys, column = d ----
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int krow = wkey0 + 8 * (r / 4) + 4 * hi + (r % 4);
-            if (krow < S) {
-                const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
-                p.dk[off] = (__bf16)(dkacc[db][r] * p.scale);
-                p.dv[off] = (__bf16)dvacc[db][r];
-            }
-        }
-}
 
 // ------------------------------------------------------------------ dQ
 constexpr int DQ_BM = 128;  // query rows per workgroup (32 per wave)
@@ -422,7 +256,12 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
         const int64_t blocks = (lanes + 255) / 256;
         if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, st, (const __bf16*)a.o,
-                           (const __bf16*)a.dO, a.delta, a.B, a.S, a.Hq);
+                           (const __bf16*)a.dO, a.lse, a.delta, a.lsn, a.dn, a.B, a.S, a.S_pad, a.Hq,
+                           1.0f / a.scale);
+        if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
+        const int64_t npad = (int64_t)a.B * a.Hq * (a.S_pad - a.S);
+        hipLaunchKernelGGL(aux_pad_kernel, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, st, a.lsn, a.dn,
+                           a.B * a.Hq, a.S, a.S_pad);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
     }
     BwdParams p;
@@ -433,10 +272,8 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
     if (a.stages & SP_BWD_STAGE_DKDV) {
-        p.n_tiles = (a.S + KV_BN - 1) / KV_BN;
-        dim3 grid(p.n_tiles, a.Hkv, a.B);
-        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN>), grid, dim3(kThreads), 0, st, p);
-        if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
+        const sp_status r = launch_attn_bwd_dkdv(a, st);
+        if (r != SP_OK) return r;
     }
     if (a.stages & SP_BWD_STAGE_DQ) {
         p.n_tiles = (a.S + DQ_BM - 1) / DQ_BM;

@@ -31,10 +31,13 @@ sp_status check_attn_shape(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_
 
 inline float resolve_scale(float s, int32_t D) { return s > 0.f ? s : 1.0f / sqrtf((float)D); }
 
-// Workspace layout: [delta fp32 Hq*T (bwd only)] [row_lo int32 T] [row_hi int32 T] (varlen only),
-// each part rounded up to 256 bytes.
+// Workspace layout: [delta fp32 B*Hq*S] [-LSE/scale fp32 B*Hq*S_pad] [-Delta fp32 B*Hq*S_pad] (bwd only)
+// [row_lo int32 T] [row_hi int32 T] (varlen only), each part rounded up to 256 bytes.
 size_t delta_bytes(int64_t T, int32_t Hq) { return align_up((size_t)T * (size_t)Hq * sizeof(float), 256); }
 size_t bounds_bytes(int64_t T) { return align_up((size_t)T * sizeof(int32_t), 256); }
+size_t aux_bytes(int64_t B, int64_t S, int32_t Hq) {
+    return align_up((size_t)B * (size_t)Hq * (size_t)sp::aux_pitch(S) * sizeof(float), 256);
+}
 
 }  // namespace
 
@@ -74,7 +77,7 @@ size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_
     if (n_docs < 0 || B <= 0) return 0;
     const int64_t T = n_docs > 0 ? S_or_T : B * S_or_T;
     if (check_attn_shape(n_docs > 0 ? 1 : B, S_or_T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
-    size_t n = delta_bytes(T, Hq);
+    size_t n = delta_bytes(T, Hq) + 2 * aux_bytes(n_docs > 0 ? 1 : B, S_or_T, Hq);
     if (n_docs > 0) n += 2 * bounds_bytes(T);
     return n < 256 ? 256 : n;
 }
@@ -129,6 +132,9 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
+    a.lsn = (float*)((char*)workspace + delta_bytes(B * S, Hq));
+    a.dn = (float*)((char*)a.lsn + aux_bytes(B, S, Hq));
+    a.S_pad = sp::aux_pitch(S);
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = stages;
@@ -183,13 +189,16 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     if (workspace_bytes < sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     float* delta = (float*)workspace;
-    int32_t* row_lo = (int32_t*)((char*)workspace + delta_bytes(T, Hq));
+    float* lsn = (float*)((char*)workspace + delta_bytes(T, Hq));
+    float* dn = (float*)((char*)lsn + aux_bytes(1, T, Hq));
+    int32_t* row_lo = (int32_t*)((char*)dn + aux_bytes(1, T, Hq));
     int32_t* row_hi = (int32_t*)((char*)row_lo + bounds_bytes(T));
     st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
     if (st != SP_OK) return st;
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
+    a.lsn = lsn; a.dn = dn; a.S_pad = sp::aux_pitch(T);
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;

@@ -22,6 +22,8 @@ struct AttnArgs {
     void* o; float* lse;                           // fwd outputs (bwd: inputs)
     const void* dO; void* dq; void* dk; void* dv;  // bwd only
     float* delta;                                  // bwd workspace, [B, Hq, S] fp32
+    float* lsn; float* dn;                         // bwd workspace, [B, Hq, S_pad] fp32: -LSE/scale, -Delta
+    int32_t S_pad;                                 // row pitch of lsn/dn (S rounded up to 64, plus 64)
     const int32_t* row_lo;  // varlen: first row of the row's document, [S]; null if dense
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
     int32_t B, S, Hq, Hkv, D;
@@ -35,5 +37,9 @@ sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T
                             int32_t* row_hi, hipStream_t st);
 sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
+sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);
+
+// row pitch of the per-row backward scalars
+inline int32_t aux_pitch(int64_t S) { return (int32_t)((S + 63) / 64 * 64 + 64); }
 
 }  // namespace sp
