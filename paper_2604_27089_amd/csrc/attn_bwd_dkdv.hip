@@ -6,10 +6,11 @@
 //   dK_j = scale * sum_{a in group} sum_{i>=j} dS_ij q_i,   dS_ij = P_ij (dO_i.v_j - Delta_i)
 //
 // One workgroup = 4 waves = 256 keys of one KV head, one wave per SIMD; a wave
-// owns 64 keys (two 32-key blocks): their K and V stay in registers as MFMA B
-// operands and their dK, dV live in 256 accumulator registers that only MFMAs
-// touch.  Every operand fetched from LDS therefore feeds two MFMAs, which keeps
-// the LDS traffic per flop half of what a 32-key wave would need.
+// owns 64 keys (two 32-key blocks): their K stays in registers as MFMA B operand,
+// their V sits in LDS for the whole kernel, and their dK, dV live in 256
+// accumulator registers that only MFMAs touch.  A streamed operand fetched from
+// LDS feeds two MFMAs (one per key block), which keeps the LDS traffic per flop
+// well below what a 32-key wave would need.
 //
 // The Q/dO rows of the G query heads of the group stream through LDS in tiles
 // of 64 rows (direct global->LDS loads, double-buffered, XOR-swizzled), from the
@@ -56,6 +57,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     constexpr int NDB = D / 32;  // 32-wide blocks of the head dim
     __shared__ __attribute__((aligned(1024))) __bf16 qs[2 * TILE];
     __shared__ __attribute__((aligned(1024))) __bf16 dos[2 * TILE];
+    __shared__ __attribute__((aligned(1024))) __bf16 vs[BNK * D];  // V of the workgroup's keys, resident
     __shared__ __attribute__((aligned(256))) float lss[2 * BMQ];
     __shared__ __attribute__((aligned(256))) float dns[2 * BMQ];
 
@@ -71,8 +73,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int j0 = jt * BNK;
     const int wkey0 = j0 + KPW * wave;  // first key of this wave
 
-    // resident B operands: K^T and V^T columns of this lane's two keys
-    bf16x8 kreg[2][NKK], vreg[2][NKK];
+    // resident B operand: K^T columns of this lane's two keys
+    bf16x8 kreg[2][NKK];
     int key_hi[2];  // one past the last query row that may see the key
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk) {
@@ -81,7 +83,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
             kreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
-            vreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
         }
         key_hi[kbk] = VARLEN ? p.row_hi[key_c] : S;
     }
@@ -114,6 +115,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 
     TileDma<D, BMQ, kWaves> dma;
     dma.init(wave, lane, q_row_stride);
+    {
+        // V rows j0 .. j0+255 -> LDS once (rows past the end re-read the last row; never used unmasked)
+        TileDma<D, BNK, kWaves> vdma;
+        vdma.init(wave, lane, kv_row_stride);
+        vdma.issue(vb, j0, S - 1, vs, wave);
+    }
 
     const int it_begin = j0 / BMQ;                    // tile holding the first key's own row
     const int it_end = (wg_hi_max + BMQ - 1) / BMQ;   // exclusive
@@ -143,56 +150,55 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         const uint32_t da = lds_addr(dos + buf * TILE) + mb * (32 * D * 2);
         const uint32_t la = lds_addr(lss + buf * BMQ) + mb * 128 + aoff;
         const uint32_t na = lds_addr(dns + buf * BMQ) + mb * 128 + aoff;
+        const uint32_t va = lds_addr(vs) + wave * (KPW * D * 2);             // this wave's 64 V rows
         const uint32_t qta = lds_addr(qs + buf * TILE) + mb * (32 * D * 2);   // same rows, transposing reads
         const uint32_t dta = lds_addr(dos + buf * TILE) + mb * (32 * D * 2);
 
         // ---- stage 1: S' and dP' for both key blocks ----
-        u32x4 lsv[4], dnv[4];
-        static_for<0, 4>([&](auto G4) { lsv[G4] = lds_async_b128<32 * decltype(G4)::value>(la); });
-        static_for<0, 4>([&](auto G4) { dnv[G4] = lds_async_b128<32 * decltype(G4)::value>(na); });
-        u32x4 aq[NKK], ad[NKK];
-        constexpr int kAhead = 2;
-        static_for<0, kAhead>([&](auto I) {
-            aq[I] = lds_async_b128<0>(qa + roff[I]);
-            ad[I] = lds_async_b128<0>(da + roff[I]);
-        });
-        lds_wait4<2 * kAhead + 4>(lsv[0], lsv[1], lsv[2], lsv[3]);
-        lds_wait4<2 * kAhead>(dnv[0], dnv[1], dnv[2], dnv[3]);
+        // The four accumulators are seeded straight from LDS with -LSE/scale resp. -Delta of the
+        // 16 rows a lane holds (one set of reads per accumulator, so no register copies), then
+        // accumulate in vector registers where the softmax arithmetic reads them.
+        u32x4 seed[4][4];  // [S0, S1, dP0, dP1][row quad]
+        static_for<0, 4>([&](auto G4) { seed[0][G4] = lds_async_b128<32 * decltype(G4)::value>(la); });
+        static_for<0, 4>([&](auto G4) { seed[1][G4] = lds_async_b128<32 * decltype(G4)::value>(la); });
+        static_for<0, 4>([&](auto G4) { seed[2][G4] = lds_async_b128<32 * decltype(G4)::value>(na); });
+        static_for<0, 4>([&](auto G4) { seed[3][G4] = lds_async_b128<32 * decltype(G4)::value>(na); });
+        static_for<0, 4>([&](auto A) { lds_wait4<4 * (3 - decltype(A)::value)>(seed[A][0], seed[A][1], seed[A][2], seed[A][3]); });
         f32x16 sacc[2], pacc[2];
-        f32x16 ls16, dn16;  // accumulator initial values: -LSE/scale and -Delta of the 16 rows this lane holds
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             // (go through scalars: bit-casting a vector element expression directly is not reliable)
-            const uint32_t lu = lsv[r / 4][r % 4], du = dnv[r / 4][r % 4];
-            ls16[r] = __uint_as_float(lu);
-            dn16[r] = __uint_as_float(du);
+            const uint32_t u0 = seed[0][r / 4][r % 4], u1 = seed[1][r / 4][r % 4];
+            const uint32_t u2 = seed[2][r / 4][r % 4], u3 = seed[3][r / 4][r % 4];
+            sacc[0][r] = __uint_as_float(u0); sacc[1][r] = __uint_as_float(u1);
+            pacc[0][r] = __uint_as_float(u2); pacc[1][r] = __uint_as_float(u3);
         }
+        u32x4 aq[NKK], ad[NKK], bv0[NKK], bv1[NKK];
+        constexpr int kAhead = 2;
+        auto load1 = [&](auto KK) __attribute__((always_inline)) {
+            constexpr int kk = decltype(KK)::value;
+            aq[kk] = lds_async_b128<0>(qa + roff[kk]);
+            ad[kk] = lds_async_b128<0>(da + roff[kk]);
+            bv0[kk] = lds_async_b128<0>(va + roff[kk]);
+            bv1[kk] = lds_async_b128<32 * D * 2>(va + roff[kk]);
+        };
+        static_for<0, kAhead>([&](auto I) { load1(I); });
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, NKK>([&](auto KK) {
             constexpr int kk = decltype(KK)::value;
-            if constexpr (kk + kAhead < NKK) {
-                aq[kk + kAhead] = lds_async_b128<0>(qa + roff[kk + kAhead]);
-                ad[kk + kAhead] = lds_async_b128<0>(da + roff[kk + kAhead]);
-            }
-            constexpr int younger = 2 * ((kk + kAhead < NKK ? kAhead : NKK - 1 - kk));  // reads issued after ad[kk]
-            lds_wait<younger + 1>(aq[kk]);
-            if constexpr (kk == 0) {
-                sacc[0] = mfma32(as_bf16x8(aq[kk]), kreg[0][kk], ls16);
-                sacc[1] = mfma32(as_bf16x8(aq[kk]), kreg[1][kk], ls16);
-            } else {
-                sacc[0] = mfma32(as_bf16x8(aq[kk]), kreg[0][kk], sacc[0]);
-                sacc[1] = mfma32(as_bf16x8(aq[kk]), kreg[1][kk], sacc[1]);
-            }
-            lds_wait<younger>(ad[kk]);
-            if constexpr (kk == 0) {
-                pacc[0] = mfma32(as_bf16x8(ad[kk]), vreg[0][kk], dn16);
-                pacc[1] = mfma32(as_bf16x8(ad[kk]), vreg[1][kk], dn16);
-            } else {
-                pacc[0] = mfma32(as_bf16x8(ad[kk]), vreg[0][kk], pacc[0]);
-                pacc[1] = mfma32(as_bf16x8(ad[kk]), vreg[1][kk], pacc[1]);
-            }
+            if constexpr (kk + kAhead < NKK) load1(std::integral_constant<int, kk + kAhead>{});
+            constexpr int m4 = 4 * ((kk + kAhead < NKK ? kAhead : NKK - 1 - kk));  // reads of later groups in flight
+            lds_wait<m4 + 3>(aq[kk]);
+            mfma32_v(sacc[0], aq[kk], kreg[0][kk]);
+            mfma32_v(sacc[1], aq[kk], kreg[1][kk]);
+            lds_wait<m4 + 1>(ad[kk]);
+            lds_wait<m4 + 1>(bv0[kk]);
+            mfma32_v(pacc[0], ad[kk], bv0[kk]);
+            lds_wait<m4>(bv1[kk]);
+            mfma32_v(pacc[1], ad[kk], bv1[kk]);
             __builtin_amdgcn_sched_barrier(0);
         });
+        mfma_results_ready(sacc[0], sacc[1], pacc[0], pacc[1]);
 
         constexpr int N3 = 2 * NDB;  // stage-3 iterations: (16-row step c, d block db)
         constexpr int kAhead3 = 2;

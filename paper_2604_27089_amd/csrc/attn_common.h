@@ -175,6 +175,33 @@ __device__ __forceinline__ void lds_wait(u32x2& x, u32x2& y) {
     asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
 }
 
+// ---------------------------------------------------------------------------
+// MFMA pinned to vector registers.
+//
+// In a kernel that may use more than 256 registers the compiler is free to put
+// any MFMA accumulator into the accumulation registers, and does so even for
+// tiles the vector ALU has to read and seed, paying a move per register each
+// way.  These two helpers issue the MFMA as opaque assembly whose accumulator
+// is constrained to vector registers.  The compiler then no longer knows the
+// instruction is an MFMA, so the caller owns the data hazards:
+//   - mfma32_v results may be read by non-MFMA instructions only after
+//     mfma_results_ready(...), which spends the wait states an 8- or 16-pass
+//     MFMA needs before its destination is readable (and ties the values so no
+//     use can be scheduled before it);
+//   - operands written by vector-ALU instructions need two wait states before
+//     the MFMA (operands arriving from LDS only need their s_waitcnt);
+//   - back-to-back MFMAs on the same accumulator are interlocked by hardware.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const u32x4& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
 // Per-lane description of the DMA loads that fill one ROWS x D tile with NW waves.
 // (NW waves).  Instruction i (0 .. ROWS*CH/64-1) covers 64/CH rows; wave w issues i = w, w+NW, ...
 // `wave` must be wave-uniform in the scalar sense (readfirstlane) so that LDS
