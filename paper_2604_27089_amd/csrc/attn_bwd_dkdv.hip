@@ -88,9 +88,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     }
     int wave_hi_min = S, wave_hi_max = S, wg_hi_max = S;
     if (VARLEN) {
-        wave_hi_min = p.row_hi[(wkey0 < S ? wkey0 : S - 1)];
-        wave_hi_max = p.row_hi[(wkey0 + KPW - 1 < S ? wkey0 + KPW - 1 : S - 1)];
-        wg_hi_max = p.row_hi[(j0 + BNK - 1 < S ? j0 + BNK - 1 : S - 1)];
+        wave_hi_min = __builtin_amdgcn_readfirstlane(p.row_hi[(wkey0 < S ? wkey0 : S - 1)]);
+        wave_hi_max = __builtin_amdgcn_readfirstlane(p.row_hi[(wkey0 + KPW - 1 < S ? wkey0 + KPW - 1 : S - 1)]);
+        wg_hi_max = __builtin_amdgcn_readfirstlane(p.row_hi[(j0 + BNK - 1 < S ? j0 + BNK - 1 : S - 1)]);
     }
 
     f32x16 dkacc[2][NDB], dvacc[2][NDB];

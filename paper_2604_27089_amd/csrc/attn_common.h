@@ -189,14 +189,23 @@ __device__ __forceinline__ void lds_wait(u32x2& x, u32x2& y) {
 //     MFMA needs before its destination is readable (and ties the values so no
 //     use can be scheduled before it);
 //   - operands written by vector-ALU instructions need two wait states before
-//     the MFMA (operands arriving from LDS only need their s_waitcnt);
+//     the MFMA.  The compiler may park resident operands in accumulation
+//     registers and copy them back right in front of the assembly, so the
+//     helpers always spend those two wait states themselves (s_nop 1);
 //   - back-to-back MFMAs on the same accumulator are interlocked by hardware.
+// MFMAs ignore the EXEC mask: code that contains them must only be skipped by a
+// truly scalar branch, so every wave-uniform condition guarding such code has
+// to be built from scalar values (readfirstlane anything loaded per lane).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const u32x4& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// first MFMA of a chain: the accumulator starts from zero
+__device__ __forceinline__ void mfma32_v0(f32x16& acc, const u32x4& a, const bf16x8& b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
     asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));

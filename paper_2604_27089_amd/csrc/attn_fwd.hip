@@ -80,9 +80,9 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     int row_lo = 0, wave_lo_min = 0, wave_lo_max = 0, wg_lo_min = 0;
     if (VARLEN) {
         row_lo = p.row_lo[qrow_c];
-        wave_lo_min = p.row_lo[wrow0 < S ? wrow0 : S - 1];
-        wave_lo_max = p.row_lo[(wrow0 + 31 < S ? wrow0 + 31 : S - 1)];
-        wg_lo_min = p.row_lo[i0];
+        wave_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[wrow0 < S ? wrow0 : S - 1]);
+        wave_lo_max = __builtin_amdgcn_readfirstlane(p.row_lo[(wrow0 + 31 < S ? wrow0 + 31 : S - 1)]);
+        wg_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[i0]);
     }
     const int wave_q_min = wrow0, wave_q_max = wrow0 + 31;
 

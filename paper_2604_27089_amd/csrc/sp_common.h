@@ -38,6 +38,7 @@ sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T
 sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);
+sp_status launch_attn_bwd_dq(const AttnArgs& a, hipStream_t st);
 
 // row pitch of the per-row backward scalars
 inline int32_t aux_pitch(int64_t S) { return (int32_t)((S + 63) / 64 * 64 + 64); }
