@@ -63,6 +63,40 @@ __global__ __launch_bounds__(kThreads) void relayout_kernel(const u32x4* __restr
         if (dst[u] < (IDX)n_vec) __builtin_nontemporal_store(val[u], out + (size_t)dst[u]);
 }
 
+// Fast path for power-of-two runs (every workload shape): no divisions.  One workgroup moves
+// kThreads*kUnroll consecutive vectors of one (batch, peer) slab of the head-side tensor, which is
+// contiguous there; on the sequence side the same vectors are S_l runs strided by P*run.
+// grid = (ceil(S_l*run / (kFastThreads*UNROLL)), P, B).  Block and unroll sizes come from a sweep
+// on MI355X: 512 threads with two vectors in flight each reach 5.9 TB/s on long runs (2 KB), four
+// vectors suit the 256-byte runs of K/V better; deeper unrolling loses up to 35 %.
+constexpr int kFastThreads = 512;
+template <bool TO_HEAD, int UNROLL>
+__global__ __launch_bounds__(kFastThreads) void relayout_pow2_kernel(const u32x4* __restrict__ in,
+                                                                u32x4* __restrict__ out, uint32_t slab_vec,
+                                                                uint32_t log2_run, uint32_t S_l, uint32_t P) {
+    const uint32_t p = blockIdx.y, b = blockIdx.z;
+    const uint32_t run_mask = (1u << log2_run) - 1u;
+    const size_t batch_vec = (size_t)slab_vec * P;  // vectors per batch element
+    const u32x4* src = in + (size_t)b * batch_vec;
+    u32x4* dst = out + (size_t)b * batch_vec;
+    const uint32_t head_base = p * slab_vec;        // slab p of the head-side tensor
+    const uint32_t e0 = blockIdx.x * (kFastThreads * UNROLL) + threadIdx.x;
+    u32x4 val[UNROLL];
+    uint32_t to[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t e = e0 + u * kFastThreads;        // vector inside the slab
+        const uint32_t s = e >> log2_run, r = e & run_mask;
+        const uint32_t seq_idx = ((s * P + p) << log2_run) + r;
+        const uint32_t head_idx = head_base + e;
+        to[u] = TO_HEAD ? head_idx : seq_idx;
+        if (e < slab_vec) val[u] = __builtin_nontemporal_load(src + (TO_HEAD ? seq_idx : head_idx));
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+        if (e0 + u * kFastThreads < slab_vec) __builtin_nontemporal_store(val[u], dst + to[u]);
+}
+
 }  // namespace
 
 namespace sp {
@@ -77,6 +111,21 @@ sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int
     if (blocks == 0) return SP_OK;
     if (blocks > 0x7fffffffull || run > 0xffffffffull) return SP_ERR_SHAPE;
     if ((uint64_t)S_l > 0xffffffffull) return SP_ERR_SHAPE;
+    const uint64_t slab = (uint64_t)S_l * run;  // vectors of one (batch, peer) slab
+    if ((run & (run - 1)) == 0 && slab * (uint64_t)P + 4096 < 0xffffffffull && P <= 65535 && B <= 65535) {
+        uint32_t lr = 0;
+        while ((1ull << lr) < run) ++lr;
+        const int unroll = run >= 64 ? 2 : 4;
+        const uint64_t pb = (uint64_t)kFastThreads * unroll;
+        dim3 g2((unsigned)((slab + pb - 1) / pb), (unsigned)P, (unsigned)B);
+#define SP_FAST(TH, U)                                                                                   \
+    hipLaunchKernelGGL((relayout_pow2_kernel<TH, U>), g2, dim3(kFastThreads), 0, st, (const u32x4*)in,    \
+                       (u32x4*)out, (uint32_t)slab, lr, (uint32_t)S_l, (uint32_t)P)
+        if (to_head) { if (unroll == 2) SP_FAST(true, 2); else SP_FAST(true, 4); }
+        else         { if (unroll == 2) SP_FAST(false, 2); else SP_FAST(false, 4); }
+#undef SP_FAST
+        return launch_status();
+    }
     dim3 grid((unsigned)blocks), block(kThreads);
     const bool small = n_vec + per_block < 0xffffffffull;  // every index, tail included, fits u32
 #define SP_RELAYOUT(TH, IDX)                                                                     \
