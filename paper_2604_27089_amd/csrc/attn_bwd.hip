@@ -23,9 +23,9 @@ template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o,
                                                    const __bf16* __restrict__ dO,
                                                    const float* __restrict__ lse,
-                                                   float* __restrict__ delta, float* __restrict__ lsn,
-                                                   float* __restrict__ dn, int32_t B, int32_t S,
-                                                   int32_t S_pad, int32_t Hq, float inv_scale) {
+                                                   float* __restrict__ delta, float* __restrict__ aux,
+                                                   int32_t B, int32_t S, int32_t S_pad, int32_t Hq,
+                                                   float inv_scale) {
     constexpr int LPV = D / 8;  // lanes per (row, head) vector, 16 bytes each
     const int64_t n_vec = (int64_t)B * S * Hq;
     const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;
@@ -45,23 +45,25 @@ __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o
         const int64_t b = bi / S;
         const int32_t i = (int32_t)(bi - b * S);
         delta[(b * Hq + h) * S + i] = acc;
-        // the per-row accumulator seeds of the dK/dV kernel
-        lsn[(b * Hq + h) * S_pad + i] = -lse[(b * Hq + h) * S + i] * inv_scale;
-        dn[(b * Hq + h) * S_pad + i] = -acc;
+        // the per-row accumulator seeds of the dK/dV kernel: per 32-row tile, 32 x -LSE/scale then 32 x -Delta
+        float* t = aux + ((b * Hq + h) * (S_pad / 32) + i / 32) * 64 + i % 32;
+        t[0] = -lse[(b * Hq + h) * S + i] * inv_scale;
+        t[32] = -acc;
     }
 }
 
 // zero the padding rows [S, S_pad) of the per-row scalars (they are fetched, never used unmasked)
-__global__ __launch_bounds__(256) void aux_pad_kernel(float* __restrict__ lsn, float* __restrict__ dn,
-                                                     int32_t BH, int32_t S, int32_t S_pad) {
+__global__ __launch_bounds__(256) void aux_pad_kernel(float* __restrict__ aux, int32_t BH, int32_t S,
+                                                     int32_t S_pad) {
     const int32_t pad = S_pad - S;
     const int64_t n = (int64_t)BH * pad;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= n) return;
     const int64_t bh = t / pad;
     const int32_t i = S + (int32_t)(t - bh * pad);
-    lsn[bh * S_pad + i] = 0.f;
-    dn[bh * S_pad + i] = 0.f;
+    float* dst = aux + (bh * (S_pad / 32) + i / 32) * 64 + i % 32;
+    dst[0] = 0.f;
+    dst[32] = 0.f;
 }
 
 template <int D, bool VARLEN>
@@ -71,12 +73,12 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
         const int64_t blocks = (lanes + 255) / 256;
         if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, st, (const __bf16*)a.o,
-                           (const __bf16*)a.dO, a.lse, a.delta, a.lsn, a.dn, a.B, a.S, a.S_pad, a.Hq,
+                           (const __bf16*)a.dO, a.lse, a.delta, a.aux, a.B, a.S, a.S_pad, a.Hq,
                            1.0f / a.scale);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
         const int64_t npad = (int64_t)a.B * a.Hq * (a.S_pad - a.S);
-        hipLaunchKernelGGL(aux_pad_kernel, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, st, a.lsn, a.dn,
-                           a.B * a.Hq, a.S, a.S_pad);
+        hipLaunchKernelGGL(aux_pad_kernel, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, st, a.aux, a.B * a.Hq,
+                           a.S, a.S_pad);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
     }
     if (a.stages & SP_BWD_STAGE_DKDV) {

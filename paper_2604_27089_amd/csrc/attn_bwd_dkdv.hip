@@ -8,20 +8,30 @@
 // One workgroup = 4 waves = 256 keys of one KV head, one wave per SIMD; a wave
 // owns 64 keys (two 32-key blocks): their K stays in registers as MFMA B operand,
 // their V sits in LDS for the whole kernel, and their dK, dV live in 256
-// accumulator registers that only MFMAs touch.  A streamed operand fetched from
-// LDS feeds two MFMAs (one per key block), which keeps the LDS traffic per flop
-// well below what a 32-key wave would need.
+// accumulation registers that only MFMAs touch.  A streamed operand fetched from
+// LDS feeds two MFMAs (one per key block).
 //
-// The Q/dO rows of the G query heads of the group stream through LDS in tiles
-// of 64 rows (direct global->LDS loads, double-buffered, XOR-swizzled), from the
-// last row down to the diagonal so that co-resident workgroups read the same
-// rows at the same time.  Per 32-row step and wave:
+// The Q/dO rows of the G query heads of the group stream through a ring of four
+// 32-row LDS tiles (direct global->LDS loads issued two steps ahead,
+// XOR-swizzled), from the last row down to the diagonal so that co-resident
+// workgroups read the same rows at the same time.  Per 32-row step u and wave:
 //   S' = Q.K^T - LSE/scale, dP' = dO.V^T - Delta   (the subtractions ride in the
-//        accumulator initial value, fetched per row from LDS)
-//   P = exp2(S' * scale*log2e), dS = P * dP'       (fp32 VALU, then bf16)
+//        accumulator initial value, fetched per row from LDS; masked positions
+//        start from -inf instead)
+//   P = exp2(S' * scale*log2e), dS = P * dP'       (fp32 vector ALU, then bf16)
 //   dV += P^T.dO, dK += dS^T.Q                     (P and dS accumulator tiles are
 //        already valid A operands; dO^T and Q^T come from transposing LDS reads)
-// All LDS operand reads are asynchronous with explicit partial waits.
+//
+// A lone wave issues in order, so the vector-ALU work is interleaved by hand
+// into the MFMA stream.  One loop body runs four phases of D/16 operand slots
+// (two MFMAs per slot):
+//   S(u) | dK(u-1) + first half of exp | dP(u) + second half of exp | dV(u) + dS products
+// i.e. the dK contraction of a step is deferred into the next body, where it
+// and the dP contraction give the exponentials of the new step something to
+// hide behind.  The body is straight-line code: every LDS operand read is
+// asynchronous, issued two slots ahead with exact partial waits, the tile loads
+// of step u+2 are spread over the S phase, and the body is instantiated once per
+// ring position so that all LDS addresses are immediates.
 #include "attn_common.h"
 #include "sp_common.h"
 
@@ -33,33 +43,60 @@ constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 constexpr int KPW = 64;            // keys per wave
 constexpr int BNK = KPW * kWaves;  // keys per workgroup
-constexpr int BMQ = 64;            // query rows per streamed tile (two 32-row steps)
+constexpr int BMQ = 32;            // query rows per streamed tile = one step
+constexpr int NBUF = 4;            // ring of streamed tiles
 
 struct DkdvParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* dO;
-    const float* lsn;  // -LSE/scale, [B, Hq, S_pad]
-    const float* dn;   // -Delta,     [B, Hq, S_pad]
+    const float* aux;  // per 32-row tile: 32 x -LSE/scale then 32 x -Delta; [B*Hq, S_pad/32, 2, 32]
     __bf16* dk; __bf16* dv;
     const int32_t* row_hi;
     int32_t S, S_pad, Hq, Hkv, G, n_ktiles;
     float scale, scale_log2;
 };
 
+__device__ __forceinline__ void results_ready2(f32x16& a, f32x16& b) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
+}
+template <int N>
+__device__ __forceinline__ void vmem_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <int N>
+__device__ __forceinline__ void lds_wait2(u32x4& a, u32x4& b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
 template <int N>
 __device__ __forceinline__ void lds_wait4(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
+// first MFMA of a chain: the accumulator starts from another register tile (shared by both key blocks)
+__device__ __forceinline__ void mfma32_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma32_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+
+// 16 accumulator registers from the four 16-byte per-row reads of one lane
+__device__ __forceinline__ void seeds_to_acc(f32x16& acc, const u32x4 (&s)[4]) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t u = s[r / 4][r % 4];  // (through a scalar: bit-casting a vector element expression directly is not reliable)
+        acc[r] = __uint_as_float(u);
+    }
+}
 
 template <int D, bool VARLEN>
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
-    constexpr int TILE = BMQ * D;
-    constexpr int NKK = D / 16;  // contraction steps over the head dim
+    constexpr int NS = D / 16;   // operand slots per phase (contraction steps over the head dim)
     constexpr int NDB = D / 32;  // 32-wide blocks of the head dim
-    __shared__ __attribute__((aligned(1024))) __bf16 qs[2 * TILE];
-    __shared__ __attribute__((aligned(1024))) __bf16 dos[2 * TILE];
-    __shared__ __attribute__((aligned(1024))) __bf16 vs[BNK * D];  // V of the workgroup's keys, resident
-    __shared__ __attribute__((aligned(256))) float lss[2 * BMQ];
-    __shared__ __attribute__((aligned(256))) float dns[2 * BMQ];
+    constexpr int TILE_B = BMQ * D * 2;
+    constexpr int HALF_B = 16 * D * 2;  // 16 rows of a tile
+    constexpr int QS = 0, DOS = NBUF * TILE_B, VS = 2 * NBUF * TILE_B, VW_B = KPW * D * 2;
+    constexpr int AUX = VS + kWaves * VW_B, AUX_SLOT = 1024, AUX_W = NBUF * AUX_SLOT;
+    constexpr int SMEM = AUX + kWaves * AUX_W;
+    static_assert(DOS + (NBUF - 1) * TILE_B + HALF_B < 65536, "immediate LDS offsets must fit 16 bits");
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
     const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -74,22 +111,19 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int wkey0 = j0 + KPW * wave;  // first key of this wave
 
     // resident B operand: K^T columns of this lane's two keys
-    bf16x8 kreg[2][NKK];
-    int key_hi[2];  // one past the last query row that may see the key
+    bf16x8 kreg[2][NS];
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk) {
         const int key = wkey0 + 32 * kbk + lo;
         const int key_c = key < S ? key : S - 1;
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
+        for (int kk = 0; kk < NS; ++kk) {
             kreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
         }
-        key_hi[kbk] = VARLEN ? p.row_hi[key_c] : S;
     }
-    int wave_hi_min = S, wave_hi_max = S, wg_hi_max = S;
+    int wave_hi_min = S, wg_hi_max = S;
     if (VARLEN) {
         wave_hi_min = __builtin_amdgcn_readfirstlane(p.row_hi[(wkey0 < S ? wkey0 : S - 1)]);
-        wave_hi_max = __builtin_amdgcn_readfirstlane(p.row_hi[(wkey0 + KPW - 1 < S ? wkey0 + KPW - 1 : S - 1)]);
         wg_hi_max = __builtin_amdgcn_readfirstlane(p.row_hi[(j0 + BNK - 1 < S ? j0 + BNK - 1 : S - 1)]);
     }
 
@@ -101,166 +135,301 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { dkacc[kbk][db][r] = 0.f; dvacc[kbk][db][r] = 0.f; }
 
-    // tile-invariant LDS byte offsets of this lane's operand reads
-    int roff[NKK];  // row-major operand (Q, dO rows): row lo (+32 per step), chunk 2*kk + hi
+    // LDS addresses of this lane's operand reads; everything that changes per step is an immediate
+    const uint32_t sm = lds_addr(smem);
+    uint32_t rb[NS];  // row-major operand (Q, dO rows): row lo, chunk 2*kk + hi
+    uint32_t vr[NS];  // the same chunk of this wave's V rows
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) roff[kk] = tile_off_b128<D>(lo, 2 * kk + hi);
-    int toff[2][NDB];  // transposed operand (Q^T, dO^T): rows 16*c + 8*half + 4*hi + (0..3), cols 32*db + 16*(lo/16) + lo%16
+    for (int kk = 0; kk < NS; ++kk) {
+        rb[kk] = sm + tile_off_b128<D>(lo, 2 * kk + hi);
+        vr[kk] = rb[kk] + VS + wave * VW_B;
+    }
+    uint32_t tb[2][NDB];  // transposed operand (Q^T, dO^T): rows 8*half + 4*hi + (0..3) (+16 per 16-row step), cols 32*db + ...
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
-            toff[half][db] = tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
-    const int aoff = 16 * hi;  // per-row scalars: rows 8*g + 4*hi .. +3 of a 32-row step
+            tb[half][db] = sm + tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
+    const uint32_t ab = sm + AUX + wave * AUX_W + 16 * hi;  // per-row scalars: rows 8*g4 + 4*hi .. +3
 
     TileDma<D, BMQ, kWaves> dma;
     dma.init(wave, lane, q_row_stride);
+    constexpr int PW = TileDma<D, BMQ, kWaves>::PER_WAVE;
+    constexpr int GROUP = 1 + 2 * PW;  // loads one wave issues per step: per-row scalars, Q, dO
+    static_assert(GROUP <= NS, "one load per slot of the S phase");
+
+    const int it_begin = j0 / BMQ;                   // tile holding the first key's own row
+    const int it_end = (wg_hi_max + BMQ - 1) / BMQ;  // exclusive
+    const int n_it = it_end - it_begin;
+    const int total = n_it * p.G;  // steps: (head in group, row tile) pairs, rows descending
+
+    // a step's head and row tile, walked incrementally
+    struct Cursor { int a, it; };
+    auto advance = [&](Cursor& c) __attribute__((always_inline)) {
+        if (c.it == it_begin) { c.it = it_end - 1; c.a += 1; } else { c.it -= 1; }
+    };
+    const uint32_t aux_lane_b = 16 * (lane & 15);  // 256 bytes per tile; lanes 16.. duplicate, their LDS bytes are padding
+    // the K-th load of the step at cursor c into ring position `buf`
+    auto issue_load = [&](auto KC, const Cursor& c, int buf) __attribute__((always_inline)) {
+        constexpr int K = decltype(KC)::value;
+        const int a = g * p.G + c.a;
+        if constexpr (K == 0) {
+            const char* src = reinterpret_cast<const char*>(p.aux) +
+                              (((size_t)b * p.Hq + a) * (p.S_pad / 32) + c.it) * 256;
+            dma16(src + aux_lane_b, smem + AUX + wave * AUX_W + buf * AUX_SLOT);
+        } else if constexpr (K <= PW) {
+            const __bf16* qb = p.q + ((size_t)b * S * p.Hq + a) * D;
+            dma.template issue_one<K - 1>(qb, c.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + QS + buf * TILE_B), wave);
+        } else {
+            const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + a) * D;
+            dma.template issue_one<K - 1 - PW>(dob, c.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + DOS + buf * TILE_B), wave);
+        }
+    };
+
+    // ---- prologue: V (resident), a finite stand-in tile for the deferred dK of "step -1", steps 0 and 1 ----
+    Cursor cc = {0, it_end - 1};  // step being computed
+    Cursor dc = cc;               // step being loaded
+    int d_left = total - 1;       // steps the load cursor may still advance
+    int steps_left = total;       // real steps not yet computed (the count is padded to a multiple of four)
     {
-        // V rows j0 .. j0+255 -> LDS once (rows past the end re-read the last row; never used unmasked)
         TileDma<D, BNK, kWaves> vdma;
         vdma.init(wave, lane, kv_row_stride);
-        vdma.issue(vb, j0, S - 1, vs, wave);
+        vdma.issue(vb, j0, S - 1, reinterpret_cast<__bf16*>(smem + VS), wave);
+        const __bf16* qb = p.q + ((size_t)b * S * p.Hq + g * p.G) * D;
+        static_for<0, PW>([&](auto K) {
+            dma.template issue_one<decltype(K)::value>(qb, cc.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + QS + 3 * TILE_B), wave);
+        });
+        static_for<0, GROUP>([&](auto K) { issue_load(K, dc, 0); });
+        if (d_left > 0) { advance(dc); --d_left; }
+        static_for<0, GROUP>([&](auto K) { issue_load(K, dc, 1); });
+        if (d_left > 0) { advance(dc); --d_left; }
+        vmem_wait<GROUP>();  // everything but the loads of step 1 has landed (this wave's share) ...
+        __builtin_amdgcn_s_barrier();  // ... and everybody else's
     }
 
-    const int it_begin = j0 / BMQ;                    // tile holding the first key's own row
-    const int it_end = (wg_hi_max + BMQ - 1) / BMQ;   // exclusive
-    const int n_it = it_end - it_begin;
-    const int total = n_it * p.G;                     // (head in group, row tile) pairs, rows descending
+    f32x16 sacc[2], pacc[2];
+    u32x4 pp[2][2], dsp[2][2];  // bf16 A operands [key block][16-row half]: P of the step, dS of the previous step
+#pragma unroll
+    for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) { dsp[kbk][c] = u32x4{0, 0, 0, 0}; pp[kbk][c] = u32x4{0, 0, 0, 0}; }
 
-    auto issue_tile = [&](int step, int buf) __attribute__((always_inline)) {
-        const int a = g * p.G + step / n_it;
-        const int i0 = (it_end - 1 - step % n_it) * BMQ;
-        const __bf16* qb = p.q + ((size_t)b * S * p.Hq + a) * D;
-        const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + a) * D;
-        dma.issue(qb, i0, S - 1, qs + buf * TILE, wave);
-        dma.issue(dob, i0, S - 1, dos + buf * TILE, wave);
-        if (wave == 0 && lane < 16) {  // 64 floats = 16 lanes x 16 bytes; the arrays are padded past S
-            const size_t base = ((size_t)b * p.Hq + a) * p.S_pad + i0;
-            dma16(p.lsn + base + 4 * lane, lss + buf * BMQ);
-            dma16(p.dn + base + 4 * lane, dns + buf * BMQ);
+    // The operand slots of a body, x = 0 .. 4*NS-1 in the phases S | dK | dP | dV.  Reads of slot x are issued
+    // ahead(x) slots early, possibly from the previous body (slots x >= 4*NS name slots of the next body).
+    constexpr int P4 = 4 * NS;
+    auto nreads = [](int x) constexpr {  // LDS reads of slot x (first S and dP slots: plus the four per-row reads)
+        const int s = x % P4;
+        return s == 0 ? 5 : s < NS ? 1 : s < 2 * NS ? 2 : s == 2 * NS ? 7 : s < 3 * NS ? 3 : 2;
+    };
+    auto ahead = [](int x) constexpr {
+        const int s = x % P4;
+        return (s >= 2 * NS && s < 3 * NS) ? 3 : 4;
+    };
+    constexpr int kMaxAhead = 4;
+    // reads issued after those of slot s by the time slot s waits for them (none for the next body if `last`)
+    auto young_reads = [=](int s, bool last) constexpr {
+        int n = 0;
+        for (int x = s + 1; x <= s + kMaxAhead; ++x)
+            if (x - ahead(x) <= s && !(last && x >= P4)) n += nreads(x);
+        return n;
+    };
+
+    // in-flight operands (asynchronous reads: see the rule in attn_common.h)
+    u32x4 aq[NS], ad[NS], bv0[NS], bv1[NS], sds[4], sdp[4];
+    u32x2 bq0[NS], bq1[NS], bd0[NS], bd1[NS];
+
+    // reads of slot s (0 .. 4*NS-1) of the body at ring position BUF
+    auto issue_reads = [&](auto BUFC, auto SC) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(BUFC)::value, PBUF = (BUF + 3) % NBUF, s = decltype(SC)::value;
+        if constexpr (s < NS) {
+            if constexpr (s == 0) static_for<0, 4>([&](auto G4) { sds[G4] = lds_async_b128<BUF * AUX_SLOT + 32 * decltype(G4)::value>(ab); });
+            aq[s] = lds_async_b128<QS + BUF * TILE_B>(rb[s]);
+        } else if constexpr (s < 2 * NS) {
+            constexpr int t = s - NS, c = t / NDB, db = t % NDB;
+            bq0[t] = lds_async_tr16<QS + PBUF * TILE_B + c * HALF_B>(tb[0][db]);
+            bq1[t] = lds_async_tr16<QS + PBUF * TILE_B + c * HALF_B>(tb[1][db]);
+        } else if constexpr (s < 3 * NS) {
+            constexpr int kk = s - 2 * NS;
+            if constexpr (kk == 0) static_for<0, 4>([&](auto G4) { sdp[G4] = lds_async_b128<BUF * AUX_SLOT + 128 + 32 * decltype(G4)::value>(ab); });
+            ad[kk] = lds_async_b128<DOS + BUF * TILE_B>(rb[kk]);
+            bv0[kk] = lds_async_b128<0>(vr[kk]);
+            bv1[kk] = lds_async_b128<32 * D * 2>(vr[kk]);
+        } else {
+            constexpr int t = s - 3 * NS, c = t / NDB, db = t % NDB;
+            bd0[t] = lds_async_tr16<DOS + BUF * TILE_B + c * HALF_B>(tb[0][db]);
+            bd1[t] = lds_async_tr16<DOS + BUF * TILE_B + c * HALF_B>(tb[1][db]);
         }
     };
 
-    // one 32-row step: rows q0 .. q0+31, operands in buffer `buf`, rows 32*mb.. of the tile
-    auto step32 = [&](int buf, int mb, int q0) __attribute__((always_inline)) {
-        bool active = q0 + 31 >= wkey0 && q0 < S;
-        if (VARLEN) active = active && q0 < wave_hi_max;
-        if (!active) return;
-        const uint32_t qa = lds_addr(qs + buf * TILE) + mb * (32 * D * 2);
-        const uint32_t da = lds_addr(dos + buf * TILE) + mb * (32 * D * 2);
-        const uint32_t la = lds_addr(lss + buf * BMQ) + mb * 128 + aoff;
-        const uint32_t na = lds_addr(dns + buf * BMQ) + mb * 128 + aoff;
-        const uint32_t va = lds_addr(vs) + wave * (KPW * D * 2);             // this wave's 64 V rows
-        const uint32_t qta = lds_addr(qs + buf * TILE) + mb * (32 * D * 2);   // same rows, transposing reads
-        const uint32_t dta = lds_addr(dos + buf * TILE) + mb * (32 * D * 2);
+    // One body = step u at ring position BUF: (BUF+3)%4 holds step u-1 (its dK is done here), (BUF+1)%4 step
+    // u+1, (BUF+2)%4 receives step u+2.  FIRST: nothing was prefetched for this body (it follows the loop
+    // back-edge, which asynchronous values must not cross); LAST: it prefetches nothing for the next body.
+    // In the very first body the deferred dK multiplies zeros by the stand-in tile.
+    auto body = [&](auto BUFC, auto FIRSTC, auto LASTC) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(BUFC)::value, DBUF = (BUF + 2) % NBUF;
+        constexpr bool FIRST = decltype(FIRSTC)::value, LAST = decltype(LASTC)::value;
+        using NextBuf = std::integral_constant<int, (BUF + 1) % NBUF>;
 
-        // ---- stage 1: S' and dP' for both key blocks ----
-        // The four accumulators are seeded straight from LDS with -LSE/scale resp. -Delta of the
-        // 16 rows a lane holds (one set of reads per accumulator, so no register copies), then
-        // accumulate in vector registers where the softmax arithmetic reads them.
-        u32x4 seed[4][4];  // [S0, S1, dP0, dP1][row quad]
-        static_for<0, 4>([&](auto G4) { seed[0][G4] = lds_async_b128<32 * decltype(G4)::value>(la); });
-        static_for<0, 4>([&](auto G4) { seed[1][G4] = lds_async_b128<32 * decltype(G4)::value>(la); });
-        static_for<0, 4>([&](auto G4) { seed[2][G4] = lds_async_b128<32 * decltype(G4)::value>(na); });
-        static_for<0, 4>([&](auto G4) { seed[3][G4] = lds_async_b128<32 * decltype(G4)::value>(na); });
-        static_for<0, 4>([&](auto A) { lds_wait4<4 * (3 - decltype(A)::value)>(seed[A][0], seed[A][1], seed[A][2], seed[A][3]); });
-        f32x16 sacc[2], pacc[2];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            // (go through scalars: bit-casting a vector element expression directly is not reliable)
-            const uint32_t u0 = seed[0][r / 4][r % 4], u1 = seed[1][r / 4][r % 4];
-            const uint32_t u2 = seed[2][r / 4][r % 4], u3 = seed[3][r / 4][r % 4];
-            sacc[0][r] = __uint_as_float(u0); sacc[1][r] = __uint_as_float(u1);
-            pacc[0][r] = __uint_as_float(u2); pacc[1][r] = __uint_as_float(u3);
-        }
-        u32x4 aq[NKK], ad[NKK], bv0[NKK], bv1[NKK];
-        constexpr int kAhead = 2;
-        auto load1 = [&](auto KK) __attribute__((always_inline)) {
-            constexpr int kk = decltype(KK)::value;
-            aq[kk] = lds_async_b128<0>(qa + roff[kk]);
-            ad[kk] = lds_async_b128<0>(da + roff[kk]);
-            bv0[kk] = lds_async_b128<0>(va + roff[kk]);
-            bv1[kk] = lds_async_b128<32 * D * 2>(va + roff[kk]);
+        // exponentials of accumulator element i (0..31) of the step; every second one also packs a pair
+        auto exp_elem = [&](auto IC) __attribute__((always_inline)) {
+            constexpr int i = decltype(IC)::value, kbk = i / 16, r = i % 16;
+            sacc[kbk][r] = __builtin_amdgcn_exp2f(sacc[kbk][r] * p.scale_log2);  // P stays in the S' registers
+            if constexpr (r % 2 == 1) pp[kbk][r / 8][(r % 8) / 2] = pack_bf16(sacc[kbk][r - 1], sacc[kbk][r]);
         };
-        static_for<0, kAhead>([&](auto I) { load1(I); });
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<0, NKK>([&](auto KK) {
-            constexpr int kk = decltype(KK)::value;
-            if constexpr (kk + kAhead < NKK) load1(std::integral_constant<int, kk + kAhead>{});
-            constexpr int m4 = 4 * ((kk + kAhead < NKK ? kAhead : NKK - 1 - kk));  // reads of later groups in flight
-            lds_wait<m4 + 3>(aq[kk]);
-            mfma32_v(sacc[0], aq[kk], kreg[0][kk]);
-            mfma32_v(sacc[1], aq[kk], kreg[1][kk]);
-            lds_wait<m4 + 1>(ad[kk]);
-            lds_wait<m4 + 1>(bv0[kk]);
-            mfma32_v(pacc[0], ad[kk], bv0[kk]);
-            lds_wait<m4>(bv1[kk]);
-            mfma32_v(pacc[1], ad[kk], bv1[kk]);
+        // dS of the pair j (0..15)
+        auto ds_pair = [&](auto JC) __attribute__((always_inline)) {
+            constexpr int j = decltype(JC)::value, kbk = j / 8, r = 2 * (j % 8);
+            uint32_t w = pack_bf16(sacc[kbk][r] * pacc[kbk][r], sacc[kbk][r + 1] * pacc[kbk][r + 1]);
+            asm volatile("" : "+v"(w));  // pins the arithmetic here: its only consumers are in the next body
+            dsp[kbk][r / 8][(r % 8) / 2] = w;
+        };
+        constexpr int EPM = 32 / (4 * NS);  // exponentials per MFMA in the dK and dP phases
+        constexpr int PPM = 16 / (2 * NS);  // dS pairs per MFMA in the dV phase
+
+        if constexpr (FIRST) {
+            static_for<0, kMaxAhead>([&](auto XC) {
+                if constexpr (decltype(XC)::value - ahead(decltype(XC)::value) < 0) issue_reads(BUFC, XC);
+            });
+        }
+        static_for<0, P4>([&](auto SC) {
+            constexpr int s = decltype(SC)::value;
+            constexpr int young = young_reads(s, LAST);  // reads allowed to stay in flight
             __builtin_amdgcn_sched_barrier(0);
-        });
-        mfma_results_ready(sacc[0], sacc[1], pacc[0], pacc[1]);
-
-        constexpr int N3 = 2 * NDB;  // stage-3 iterations: (16-row step c, d block db)
-        constexpr int kAhead3 = 2;
-        u32x2 bd0[N3], bd1[N3], bq0[N3], bq1[N3];
-        auto load3 = [&](auto T) __attribute__((always_inline)) {
-            constexpr int t = decltype(T)::value, c = t / NDB, db = t % NDB;
-            bd0[t] = lds_async_tr16<c * (16 * D * 2)>(dta + toff[0][db]);
-            bd1[t] = lds_async_tr16<c * (16 * D * 2)>(dta + toff[1][db]);
-            bq0[t] = lds_async_tr16<c * (16 * D * 2)>(qta + toff[0][db]);
-            bq1[t] = lds_async_tr16<c * (16 * D * 2)>(qta + toff[1][db]);
-        };
-
-        // ---- stage 2: P = exp2(S' * scale*log2e), dS = P * dP' ----
-        bool need_mask = q0 < wkey0 + KPW - 1 || q0 + 31 >= wave_hi_min;
-        u32x4 pp[2][2], dsp[2][2];  // bf16 A operands: [key block][16-row step]
-#pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) {
-            const int key = wkey0 + 32 * kbk + lo;
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float p0 = __builtin_amdgcn_exp2f(sacc[kbk][r] * p.scale_log2);
-                float p1 = __builtin_amdgcn_exp2f(sacc[kbk][r + 1] * p.scale_log2);
-                if (need_mask) {
-                    const int qr0 = q0 + 8 * (r / 4) + 4 * hi + (r % 4);
-                    p0 = (qr0 >= key && qr0 < key_hi[kbk]) ? p0 : 0.f;
-                    p1 = (qr0 + 1 >= key && qr0 + 1 < key_hi[kbk]) ? p1 : 0.f;
-                }
-                const float d0 = p0 * pacc[kbk][r], d1 = p1 * pacc[kbk][r + 1];
-                pp[kbk][r / 8][(r % 8) / 2] = pack_bf16(p0, p1);
-                dsp[kbk][r / 8][(r % 8) / 2] = pack_bf16(d0, d1);
+            if constexpr (s == 2 * NS) {
+                // Everybody is past the dK phase: nobody reads ring position (BUF+3)%4 any more.  This wave's
+                // loads of step u+1 have landed (those of step u+2, issued in this body, may be in flight);
+                // after the barrier so have everybody's.
+                vmem_wait<GROUP>();
+                __builtin_amdgcn_s_barrier();
             }
-        }
+            static_for<1, kMaxAhead + 1>([&](auto AC) {
+                constexpr int x = s + decltype(AC)::value;
+                if constexpr (x - ahead(x) == s) {
+                    if constexpr (x < P4) issue_reads(BUFC, std::integral_constant<int, x>{});
+                    else if constexpr (!LAST) issue_reads(NextBuf{}, std::integral_constant<int, x - P4>{});
+                }
+            });
+            if constexpr (s < NS) {
+                // ---- S(u); the loads of step u+2 ----
+                if constexpr (s == 0) {
+                    lds_wait4<young + 1>(sds[0], sds[1], sds[2], sds[3]);
+                    f32x16 seed;
+                    seeds_to_acc(seed, sds);
+                    lds_wait<young>(aq[s]);
+                    mfma32_vc(sacc[0], aq[s], kreg[0][s], seed);
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue_load(std::integral_constant<int, 0>{}, dc, DBUF);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma32_vc(sacc[1], aq[s], kreg[1][s], seed);
+                } else {
+                    lds_wait<young>(aq[s]);
+                    mfma32_v(sacc[0], aq[s], kreg[0][s]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (s < GROUP) issue_load(std::integral_constant<int, s>{}, dc, DBUF);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma32_v(sacc[1], aq[s], kreg[1][s]);
+                }
+            } else if constexpr (s < 2 * NS) {
+                // ---- dK(u-1), exponentials of key block 0 ----
+                constexpr int t = s - NS, c = t / NDB, db = t % NDB;
+                lds_wait<young>(bq0[t], bq1[t]);
+                const u32x4 bqt = {bq0[t][0], bq0[t][1], bq1[t][0], bq1[t][1]};
+                dkacc[0][db] = mfma32(as_bf16x8(dsp[0][c]), as_bf16x8(bqt), dkacc[0][db]);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (t == 0) {
+                    results_ready2(sacc[0], sacc[1]);
+                    // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
+                    const int q0 = cc.it * BMQ;
+                    const bool real = steps_left > 0;
+                    if (!real || q0 < wkey0 + KPW - 1 || q0 + 31 >= wave_hi_min) {  // rare
+                        asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
+#pragma unroll
+                        for (int kbk = 0; kbk < 2; ++kbk) {
+                            const int key = wkey0 + 32 * kbk + (int)(__lane_id() & 31);
+                            const int key_hi = VARLEN ? p.row_hi[key < S ? key : S - 1] : S;  // one past the last row that may see the key
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = q0 + 8 * (r / 4) + 4 * (int)(__lane_id() >> 5) + (r % 4);
+                                const bool vis = real && row >= key && row < key_hi;
+                                sacc[kbk][r] = vis ? sacc[kbk][r] : -__builtin_inff();
+                            }
+                        }
+                    }
+                }
+                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * t) * EPM + decltype(E)::value>{}); });
+                __builtin_amdgcn_sched_barrier(0);
+                dkacc[1][db] = mfma32(as_bf16x8(dsp[1][c]), as_bf16x8(bqt), dkacc[1][db]);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * t + 1) * EPM + decltype(E)::value>{}); });
+            } else if constexpr (s < 3 * NS) {
+                // ---- dP(u), exponentials of key block 1 ----
+                constexpr int kk = s - 2 * NS;
+                if constexpr (kk == 0) {
+                    lds_wait4<young + 3>(sdp[0], sdp[1], sdp[2], sdp[3]);
+                    f32x16 seed;
+                    seeds_to_acc(seed, sdp);
+                    lds_wait2<young + 1>(ad[kk], bv0[kk]);
+                    mfma32_vc(pacc[0], ad[kk], bv0[kk], seed);
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk)) * EPM + decltype(E)::value>{}); });
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_wait<young>(bv1[kk]);
+                    mfma32_vc(pacc[1], ad[kk], bv1[kk], seed);
+                } else {
+                    lds_wait2<young + 1>(ad[kk], bv0[kk]);
+                    mfma32_v(pacc[0], ad[kk], bv0[kk]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk)) * EPM + decltype(E)::value>{}); });
+                    __builtin_amdgcn_sched_barrier(0);
+                    lds_wait<young>(bv1[kk]);
+                    mfma32_v(pacc[1], ad[kk], bv1[kk]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk) + 1) * EPM + decltype(E)::value>{}); });
+            } else {
+                // ---- dV(u), dS products ----
+                constexpr int t = s - 3 * NS, c = t / NDB, db = t % NDB;
+                lds_wait<young>(bd0[t], bd1[t]);
+                const u32x4 bdo = {bd0[t][0], bd0[t][1], bd1[t][0], bd1[t][1]};
+                dvacc[0][db] = mfma32(as_bf16x8(pp[0][c]), as_bf16x8(bdo), dvacc[0][db]);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (t == 0) results_ready2(pacc[0], pacc[1]);
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
+                __builtin_amdgcn_sched_barrier(0);
+                dvacc[1][db] = mfma32(as_bf16x8(pp[1][c]), as_bf16x8(bdo), dvacc[1][db]);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
+            }
+        });
         __builtin_amdgcn_sched_barrier(0);
+        --steps_left;
+        if (steps_left > 0) advance(cc);
+        if (d_left > 0) { advance(dc); --d_left; }
+    };
 
-        // ---- stage 3: dV += P^T.dO, dK += dS^T.Q ----
-        static_for<0, kAhead3>([&](auto T) { load3(T); });
-        static_for<0, N3>([&](auto T) {
-            constexpr int t = decltype(T)::value, c = t / NDB, db = t % NDB;
-            if constexpr (t + kAhead3 < N3) load3(std::integral_constant<int, t + kAhead3>{});
-            constexpr int ahead = (t + kAhead3 < N3 ? kAhead3 : N3 - 1 - t);  // younger iterations in flight
-            lds_wait<4 * ahead + 2>(bd0[t], bd1[t]);
-            const u32x4 bdo = {bd0[t][0], bd0[t][1], bd1[t][0], bd1[t][1]};
-            dvacc[0][db] = mfma32(as_bf16x8(pp[0][c]), as_bf16x8(bdo), dvacc[0][db]);
-            dvacc[1][db] = mfma32(as_bf16x8(pp[1][c]), as_bf16x8(bdo), dvacc[1][db]);
-            lds_wait<4 * ahead>(bq0[t], bq1[t]);
-            const u32x4 bqt = {bq0[t][0], bq0[t][1], bq1[t][0], bq1[t][1]};
+    // Four steps per iteration, one per ring position; the step count is rounded up to a multiple of four
+    // with steps whose P is all zero (they re-read the last tile).
+    for (int u = 0; u < total; u += NBUF) {
+        body(std::integral_constant<int, 0>{}, std::true_type{}, std::false_type{});
+        body(std::integral_constant<int, 1>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 2>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 3>{}, std::false_type{}, std::true_type{});
+    }
+
+    // ---- the deferred dK of the last step ----
+    {
+        constexpr uint32_t qoff = QS + (NBUF - 1) * TILE_B;
+        static_for<0, NS>([&](auto TC) {
+            constexpr int t = decltype(TC)::value, c = t / NDB, db = t % NDB;
+            u32x2 h0 = lds_async_tr16<c * HALF_B>(tb[0][db] + qoff);
+            u32x2 h1 = lds_async_tr16<c * HALF_B>(tb[1][db] + qoff);
+            lds_wait<0>(h0, h1);
+            const u32x4 bqt = {h0[0], h0[1], h1[0], h1[1]};
             dkacc[0][db] = mfma32(as_bf16x8(dsp[0][c]), as_bf16x8(bqt), dkacc[0][db]);
             dkacc[1][db] = mfma32(as_bf16x8(dsp[1][c]), as_bf16x8(bqt), dkacc[1][db]);
-            __builtin_amdgcn_sched_barrier(0);
         });
-    };
-
-    if (total > 0) issue_tile(0, 0);
-    for (int step = 0; step < total; ++step) {
-        const int buf = step & 1;
-        wait_vmem();      // this wave's share of tile `step` is in LDS
-        __syncthreads();  // ... and everybody else's; everybody is done reading the other buffer
-        if (step + 1 < total) issue_tile(step + 1, buf ^ 1);
-        const int i0 = (it_end - 1 - step % n_it) * BMQ;
-        step32(buf, 1, i0 + 32);
-        step32(buf, 0, i0);
     }
+    wait_vmem();  // no direct-to-LDS load may outlive the workgroup's LDS allocation
 
     // ---- write dK (scaled) and dV: accumulator rows = keys, column = d ----
 #pragma unroll
@@ -282,7 +451,7 @@ template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
     DkdvParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
-    p.lsn = a.lsn; p.dn = a.dn; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
+    p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
     p.S = a.S; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.n_ktiles = (a.S + BNK - 1) / BNK;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;

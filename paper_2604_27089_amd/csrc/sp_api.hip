@@ -31,7 +31,8 @@ sp_status check_attn_shape(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_
 
 inline float resolve_scale(float s, int32_t D) { return s > 0.f ? s : 1.0f / sqrtf((float)D); }
 
-// Workspace layout: [delta fp32 B*Hq*S] [-LSE/scale fp32 B*Hq*S_pad] [-Delta fp32 B*Hq*S_pad] (bwd only)
+// Workspace layout: [delta fp32 B*Hq*S] [per-row seeds fp32 2*B*Hq*S_pad: per 32-row tile, 32 x -LSE/scale
+// then 32 x -Delta] (bwd only)
 // [row_lo int32 T] [row_hi int32 T] (varlen only), each part rounded up to 256 bytes.
 size_t delta_bytes(int64_t T, int32_t Hq) { return align_up((size_t)T * (size_t)Hq * sizeof(float), 256); }
 size_t bounds_bytes(int64_t T) { return align_up((size_t)T * sizeof(int32_t), 256); }
@@ -132,8 +133,7 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
-    a.lsn = (float*)((char*)workspace + delta_bytes(B * S, Hq));
-    a.dn = (float*)((char*)a.lsn + aux_bytes(B, S, Hq));
+    a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
     a.S_pad = sp::aux_pitch(S);
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
@@ -189,16 +189,15 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     if (workspace_bytes < sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     float* delta = (float*)workspace;
-    float* lsn = (float*)((char*)workspace + delta_bytes(T, Hq));
-    float* dn = (float*)((char*)lsn + aux_bytes(1, T, Hq));
-    int32_t* row_lo = (int32_t*)((char*)dn + aux_bytes(1, T, Hq));
+    float* aux = (float*)((char*)workspace + delta_bytes(T, Hq));
+    int32_t* row_lo = (int32_t*)((char*)aux + 2 * aux_bytes(1, T, Hq));
     int32_t* row_hi = (int32_t*)((char*)row_lo + bounds_bytes(T));
     st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
     if (st != SP_OK) return st;
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
-    a.lsn = lsn; a.dn = dn; a.S_pad = sp::aux_pitch(T);
+    a.aux = aux; a.S_pad = sp::aux_pitch(T);
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;

@@ -22,8 +22,9 @@ struct AttnArgs {
     void* o; float* lse;                           // fwd outputs (bwd: inputs)
     const void* dO; void* dq; void* dk; void* dv;  // bwd only
     float* delta;                                  // bwd workspace, [B, Hq, S] fp32
-    float* lsn; float* dn;                         // bwd workspace, [B, Hq, S_pad] fp32: -LSE/scale, -Delta
-    int32_t S_pad;                                 // row pitch of lsn/dn (S rounded up to 64, plus 64)
+    float* aux;                                    // bwd workspace, [B*Hq, S_pad/32, 2, 32] fp32: per 32-row
+                                                   // tile, 32 x -LSE/scale then 32 x -Delta
+    int32_t S_pad;                                 // rows per head in aux (S rounded up to 64, plus 64)
     const int32_t* row_lo;  // varlen: first row of the row's document, [S]; null if dense
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
     int32_t B, S, Hq, Hkv, D;
