@@ -60,21 +60,43 @@ __device__ __forceinline__ void results_ready2(f32x16& a, f32x16& b) {
 }
 template <int N>
 __device__ __forceinline__ void vmem_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-template <int N>
-__device__ __forceinline__ void lds_wait2(u32x4& a, u32x4& b) {
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
-}
 
+// Waits that tie the values they cover: used where the awaited registers are then combined into wider
+// operands (the combination must not be scheduled before the wait).
 template <int N>
 __device__ __forceinline__ void lds_wait4(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
-// first MFMA of a chain: the accumulator starts from another register tile (shared by both key blocks)
-__device__ __forceinline__ void mfma32_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+template <int N>
+__device__ __forceinline__ void lds_wait4(u32x2& a, u32x2& b, u32x2& c, u32x2& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
-__device__ __forceinline__ void mfma32_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+
+// MFMAs as assembly.  The kernel is bound by how many instructions a lone wave can issue, so these carry
+// no padding: the callers guarantee that no vector-ALU instruction writes an operand within the two
+// instructions before (operands come from LDS reads, from earlier MFMAs or from arithmetic done at least
+// one slot earlier), and results are read by the vector ALU only after results_ready2.  Volatile
+// assembly statements keep their order, which is what orders an MFMA after the wait that covers its
+// operands.  W: the wait for the operands rides in the same statement.
+//   _v: accumulator in vector registers; _vc: ... starting from another tile; _a: in accumulation registers
+template <int W>
+__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+template <int W>
+__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const u32x4& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma_a(f32x16& acc, const u32x4& a, const u32x4& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
 // 16 accumulator registers from the four 16-byte per-row reads of one lane
@@ -152,57 +174,80 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
             tb[half][db] = sm + tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
     const uint32_t ab = sm + AUX + wave * AUX_W + 16 * hi;  // per-row scalars: rows 8*g4 + 4*hi .. +3
 
-    TileDma<D, BMQ, kWaves> dma;
-    dma.init(wave, lane, q_row_stride);
-    constexpr int PW = TileDma<D, BMQ, kWaves>::PER_WAVE;
-    constexpr int GROUP = 1 + 2 * PW;  // loads one wave issues per step: per-row scalars, Q, dO
-    static_assert(GROUP <= NS, "one load per slot of the S phase");
-
     const int it_begin = j0 / BMQ;                   // tile holding the first key's own row
     const int it_end = (wg_hi_max + BMQ - 1) / BMQ;  // exclusive
     const int n_it = it_end - it_begin;
     const int total = n_it * p.G;  // steps: (head in group, row tile) pairs, rows descending
 
-    // a step's head and row tile, walked incrementally
-    struct Cursor { int a, it; };
-    auto advance = [&](Cursor& c) __attribute__((always_inline)) {
-        if (c.it == it_begin) { c.it = it_end - 1; c.a += 1; } else { c.it -= 1; }
+    // ---- global -> LDS loads of a step: per-row scalars (1), Q rows (PW), dO rows (PW) per wave ----
+    using Dma = TileDma<D, BMQ, kWaves>;
+    constexpr int PW = Dma::PER_WAVE;
+    constexpr int GROUP = 1 + 2 * PW;
+    static_assert(GROUP <= NS, "one load per slot of the S phase");
+    const uint32_t stride_b = (uint32_t)(q_row_stride * 2);
+    // byte offset, from the tile's first row, of the 16 bytes this lane fetches in its K-th load; rows past
+    // `lim` (tile-relative) re-read row `lim` (they are never used unmasked)
+    auto lane_off = [&](int K, int lim) __attribute__((always_inline)) {
+        const int row = Dma::RPI * (wave + kWaves * K) + lane / Dma::CH;
+        const uint32_t chunk_b = (uint32_t)(((lane % Dma::CH) ^ swz<D>(row)) * 16);
+        return (uint32_t)(row < lim ? row : lim) * stride_b + chunk_b;
     };
+    uint32_t voff[PW];
+#pragma unroll
+    for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, BMQ - 1);
     const uint32_t aux_lane_b = 16 * (lane & 15);  // 256 bytes per tile; lanes 16.. duplicate, their LDS bytes are padding
-    // the K-th load of the step at cursor c into ring position `buf`
-    auto issue_load = [&](auto KC, const Cursor& c, int buf) __attribute__((always_inline)) {
+    const int it_tail = (S % BMQ != 0) ? (S - 1) / BMQ : -1;  // the tile that runs past the last row, if any
+
+    // the step being loaded: scalar byte pointers to its tile in q, dO and the per-row scalars
+    struct LoadCursor { const char* q; const char* dO; const char* aux; int it, left; };
+    LoadCursor dc;
+    {
+        const size_t head0 = ((size_t)b * S * p.Hq + (size_t)g * p.G) * D * 2;
+        dc.it = it_end - 1;
+        dc.q = reinterpret_cast<const char*>(p.q) + head0 + (size_t)dc.it * BMQ * stride_b;
+        dc.dO = reinterpret_cast<const char*>(p.dO) + head0 + (size_t)dc.it * BMQ * stride_b;
+        dc.aux = reinterpret_cast<const char*>(p.aux) + (((size_t)b * p.Hq + (size_t)g * p.G) * (p.S_pad / 32) + dc.it) * 256;
+        dc.left = total - 1;
+    }
+    const size_t tile_step_b = (size_t)BMQ * stride_b;
+    const size_t head_jump_b = (size_t)D * 2 + (size_t)(n_it - 1) * tile_step_b;          // first tile of a head -> last tile of the next
+    const size_t aux_jump_b = ((size_t)(p.S_pad / 32) + (size_t)(n_it - 1)) * 256;
+    auto advance_load = [&]() __attribute__((always_inline)) {
+        if (dc.left > 0) {  // past the last step the cursor stays (the padding steps re-read the last tile)
+            --dc.left;
+            if (dc.it == it_begin) {
+                dc.it = it_end - 1; dc.q += head_jump_b; dc.dO += head_jump_b; dc.aux += aux_jump_b;
+            } else {
+                dc.it -= 1; dc.q -= tile_step_b; dc.dO -= tile_step_b; dc.aux -= 256;
+            }
+        }
+    };
+    auto issue_load = [&](auto KC, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(KC)::value;
-        const int a = g * p.G + c.a;
         if constexpr (K == 0) {
-            const char* src = reinterpret_cast<const char*>(p.aux) +
-                              (((size_t)b * p.Hq + a) * (p.S_pad / 32) + c.it) * 256;
-            dma16(src + aux_lane_b, smem + AUX + wave * AUX_W + buf * AUX_SLOT);
-        } else if constexpr (K <= PW) {
-            const __bf16* qb = p.q + ((size_t)b * S * p.Hq + a) * D;
-            dma.template issue_one<K - 1>(qb, c.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + QS + buf * TILE_B), wave);
+            dma16(dc.aux + aux_lane_b, smem + AUX + wave * AUX_W + buf * AUX_SLOT);
         } else {
-            const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + a) * D;
-            dma.template issue_one<K - 1 - PW>(dob, c.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + DOS + buf * TILE_B), wave);
+            constexpr int KK = (K - 1) % PW;
+            uint32_t off = voff[KK];
+            if (dc.it == it_tail) off = lane_off(KK, S - 1 - dc.it * BMQ);  // rare
+            const char* src = K <= PW ? dc.q : dc.dO;
+            char* dst = smem + (K <= PW ? QS : DOS) + buf * TILE_B + (wave + kWaves * KK) * 1024;
+            dma16(src + off, dst);
         }
     };
 
     // ---- prologue: V (resident), a finite stand-in tile for the deferred dK of "step -1", steps 0 and 1 ----
-    Cursor cc = {0, it_end - 1};  // step being computed
-    Cursor dc = cc;               // step being loaded
-    int d_left = total - 1;       // steps the load cursor may still advance
-    int steps_left = total;       // real steps not yet computed (the count is padded to a multiple of four)
+    int cur_it = it_end - 1;  // row tile of the step being computed
+    int steps_left = total;   // real steps not yet computed (the count is padded to a multiple of four)
     {
         TileDma<D, BNK, kWaves> vdma;
         vdma.init(wave, lane, kv_row_stride);
         vdma.issue(vb, j0, S - 1, reinterpret_cast<__bf16*>(smem + VS), wave);
-        const __bf16* qb = p.q + ((size_t)b * S * p.Hq + g * p.G) * D;
-        static_for<0, PW>([&](auto K) {
-            dma.template issue_one<decltype(K)::value>(qb, cc.it * BMQ, S - 1, reinterpret_cast<__bf16*>(smem + QS + 3 * TILE_B), wave);
-        });
-        static_for<0, GROUP>([&](auto K) { issue_load(K, dc, 0); });
-        if (d_left > 0) { advance(dc); --d_left; }
-        static_for<0, GROUP>([&](auto K) { issue_load(K, dc, 1); });
-        if (d_left > 0) { advance(dc); --d_left; }
+        static_for<1, PW + 1>([&](auto K) { issue_load(K, 3); });  // Q rows of step 0 again, as the stand-in
+        static_for<0, GROUP>([&](auto K) { issue_load(K, 0); });
+        advance_load();
+        static_for<0, GROUP>([&](auto K) { issue_load(K, 1); });
+        advance_load();
         vmem_wait<GROUP>();  // everything but the loads of step 1 has landed (this wave's share) ...
         __builtin_amdgcn_s_barrier();  // ... and everybody else's
     }
@@ -216,6 +261,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 
     // The operand slots of a body, x = 0 .. 4*NS-1 in the phases S | dK | dP | dV.  Reads of slot x are issued
     // ahead(x) slots early, possibly from the previous body (slots x >= 4*NS name slots of the next body).
+    // Waits happen once per pair of slots, at the even one.
     constexpr int P4 = 4 * NS;
     auto nreads = [](int x) constexpr {  // LDS reads of slot x (first S and dP slots: plus the four per-row reads)
         const int s = x % P4;
@@ -226,10 +272,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         return (s >= 2 * NS && s < 3 * NS) ? 3 : 4;
     };
     constexpr int kMaxAhead = 4;
-    // reads issued after those of slot s by the time slot s waits for them (none for the next body if `last`)
+    // reads issued after those of slot s+1 by the time (even) slot s waits (none for the next body if `last`)
     auto young_reads = [=](int s, bool last) constexpr {
         int n = 0;
-        for (int x = s + 1; x <= s + kMaxAhead; ++x)
+        for (int x = s + 2; x <= s + kMaxAhead; ++x)
             if (x - ahead(x) <= s && !(last && x >= P4)) n += nreads(x);
         return n;
     };
@@ -269,12 +315,29 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         constexpr int BUF = decltype(BUFC)::value, DBUF = (BUF + 2) % NBUF;
         constexpr bool FIRST = decltype(FIRSTC)::value, LAST = decltype(LASTC)::value;
         using NextBuf = std::integral_constant<int, (BUF + 1) % NBUF>;
+        constexpr int EPM = 32 / (4 * NS);  // exponentials per MFMA in the dK and dP phases (32 MFMAs, 32 elements)
+        constexpr int PPM = 16 / (2 * NS);  // dS pairs per MFMA in the dV phase
 
-        // exponentials of accumulator element i (0..31) of the step; every second one also packs a pair
-        auto exp_elem = [&](auto IC) __attribute__((always_inline)) {
-            constexpr int i = decltype(IC)::value, kbk = i / 16, r = i % 16;
-            sacc[kbk][r] = __builtin_amdgcn_exp2f(sacc[kbk][r] * p.scale_log2);  // P stays in the S' registers
-            if constexpr (r % 2 == 1) pp[kbk][r / 8][(r % 8) / 2] = pack_bf16(sacc[kbk][r - 1], sacc[kbk][r]);
+        // Vector-ALU work of MFMA position m (0 .. 4*NS-1) of the dK and dP phases: the exponentials of
+        // accumulator elements m*EPM .. (element i = key block i/16, register i%16; P stays in the S'
+        // registers), and the bf16 packing of the pairs completed by the previous position (so that no
+        // pack directly follows the exponential it reads).
+        auto pack_pair = [&](auto JC) __attribute__((always_inline)) {
+            constexpr int j = decltype(JC)::value, kbk = j / 8, r = 2 * (j % 8);
+            pp[kbk][r / 8][(r % 8) / 2] = pack_bf16(sacc[kbk][r], sacc[kbk][r + 1]);
+        };
+        auto exp_chunk = [&](auto MC) __attribute__((always_inline)) {
+            constexpr int m = decltype(MC)::value;
+            float t[EPM];
+            static_for<0, EPM>([&](auto E) {
+                constexpr int i = m * EPM + decltype(E)::value;
+                t[decltype(E)::value] = sacc[i / 16][i % 16] * p.scale_log2;
+            });
+            if constexpr (m > 0) static_for<((m - 1) * EPM) / 2, (m * EPM) / 2>([&](auto J) { pack_pair(J); });
+            static_for<0, EPM>([&](auto E) {
+                constexpr int i = m * EPM + decltype(E)::value;
+                sacc[i / 16][i % 16] = __builtin_amdgcn_exp2f(t[decltype(E)::value]);
+            });
         };
         // dS of the pair j (0..15)
         auto ds_pair = [&](auto JC) __attribute__((always_inline)) {
@@ -283,8 +346,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
             asm volatile("" : "+v"(w));  // pins the arithmetic here: its only consumers are in the next body
             dsp[kbk][r / 8][(r % 8) / 2] = w;
         };
-        constexpr int EPM = 32 / (4 * NS);  // exponentials per MFMA in the dK and dP phases
-        constexpr int PPM = 16 / (2 * NS);  // dS pairs per MFMA in the dV phase
 
         if constexpr (FIRST) {
             static_for<0, kMaxAhead>([&](auto XC) {
@@ -293,7 +354,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         }
         static_for<0, P4>([&](auto SC) {
             constexpr int s = decltype(SC)::value;
-            constexpr int young = young_reads(s, LAST);  // reads allowed to stay in flight
+            constexpr bool even = s % 2 == 0;
+            constexpr int W = even ? young_reads(s, LAST) : -1;  // reads allowed to stay in flight at the pair's wait
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (s == 2 * NS) {
                 // Everybody is past the dK phase: nobody reads ring position (BUF+3)%4 any more.  This wave's
@@ -309,37 +371,36 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                     else if constexpr (!LAST) issue_reads(NextBuf{}, std::integral_constant<int, x - P4>{});
                 }
             });
+            __builtin_amdgcn_sched_barrier(0);
             if constexpr (s < NS) {
                 // ---- S(u); the loads of step u+2 ----
                 if constexpr (s == 0) {
-                    lds_wait4<young + 1>(sds[0], sds[1], sds[2], sds[3]);
+                    lds_wait4<W>(sds[0], sds[1], sds[2], sds[3]);
                     f32x16 seed;
                     seeds_to_acc(seed, sds);
-                    lds_wait<young>(aq[s]);
-                    mfma32_vc(sacc[0], aq[s], kreg[0][s], seed);
+                    mfma_vc(sacc[0], aq[s], kreg[0][s], seed);
                     __builtin_amdgcn_sched_barrier(0);
-                    issue_load(std::integral_constant<int, 0>{}, dc, DBUF);
+                    issue_load(std::integral_constant<int, 0>{}, DBUF);
                     __builtin_amdgcn_sched_barrier(0);
-                    mfma32_vc(sacc[1], aq[s], kreg[1][s], seed);
+                    mfma_vc(sacc[1], aq[s], kreg[1][s], seed);
                 } else {
-                    lds_wait<young>(aq[s]);
-                    mfma32_v(sacc[0], aq[s], kreg[0][s]);
+                    mfma_v<W>(sacc[0], aq[s], kreg[0][s]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (s < GROUP) issue_load(std::integral_constant<int, s>{}, dc, DBUF);
+                    if constexpr (s < GROUP) issue_load(std::integral_constant<int, s>{}, DBUF);
                     __builtin_amdgcn_sched_barrier(0);
-                    mfma32_v(sacc[1], aq[s], kreg[1][s]);
+                    mfma_v<-1>(sacc[1], aq[s], kreg[1][s]);
                 }
             } else if constexpr (s < 2 * NS) {
                 // ---- dK(u-1), exponentials of key block 0 ----
                 constexpr int t = s - NS, c = t / NDB, db = t % NDB;
-                lds_wait<young>(bq0[t], bq1[t]);
+                if constexpr (even) lds_wait4<W>(bq0[t], bq1[t], bq0[t + 1], bq1[t + 1]);
                 const u32x4 bqt = {bq0[t][0], bq0[t][1], bq1[t][0], bq1[t][1]};
-                dkacc[0][db] = mfma32(as_bf16x8(dsp[0][c]), as_bf16x8(bqt), dkacc[0][db]);
+                mfma_a(dkacc[0][db], dsp[0][c], bqt);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (t == 0) {
                     results_ready2(sacc[0], sacc[1]);
                     // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
-                    const int q0 = cc.it * BMQ;
+                    const int q0 = cur_it * BMQ;
                     const bool real = steps_left > 0;
                     if (!real || q0 < wkey0 + KPW - 1 || q0 + 31 >= wave_hi_min) {  // rare
                         asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
@@ -356,55 +417,54 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                         }
                     }
                 }
-                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * t) * EPM + decltype(E)::value>{}); });
+                exp_chunk(std::integral_constant<int, 2 * t>{});
                 __builtin_amdgcn_sched_barrier(0);
-                dkacc[1][db] = mfma32(as_bf16x8(dsp[1][c]), as_bf16x8(bqt), dkacc[1][db]);
+                mfma_a(dkacc[1][db], dsp[1][c], bqt);
                 __builtin_amdgcn_sched_barrier(0);
-                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * t + 1) * EPM + decltype(E)::value>{}); });
+                exp_chunk(std::integral_constant<int, 2 * t + 1>{});
             } else if constexpr (s < 3 * NS) {
                 // ---- dP(u), exponentials of key block 1 ----
                 constexpr int kk = s - 2 * NS;
                 if constexpr (kk == 0) {
-                    lds_wait4<young + 3>(sdp[0], sdp[1], sdp[2], sdp[3]);
+                    lds_wait4<W>(sdp[0], sdp[1], sdp[2], sdp[3]);
                     f32x16 seed;
                     seeds_to_acc(seed, sdp);
-                    lds_wait2<young + 1>(ad[kk], bv0[kk]);
-                    mfma32_vc(pacc[0], ad[kk], bv0[kk], seed);
+                    mfma_vc(pacc[0], ad[kk], bv0[kk], seed);
                     __builtin_amdgcn_sched_barrier(0);
-                    static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk)) * EPM + decltype(E)::value>{}); });
+                    exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
                     __builtin_amdgcn_sched_barrier(0);
-                    lds_wait<young>(bv1[kk]);
-                    mfma32_vc(pacc[1], ad[kk], bv1[kk], seed);
+                    mfma_vc(pacc[1], ad[kk], bv1[kk], seed);
                 } else {
-                    lds_wait2<young + 1>(ad[kk], bv0[kk]);
-                    mfma32_v(pacc[0], ad[kk], bv0[kk]);
+                    mfma_v<W>(pacc[0], ad[kk], bv0[kk]);
                     __builtin_amdgcn_sched_barrier(0);
-                    static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk)) * EPM + decltype(E)::value>{}); });
+                    exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
                     __builtin_amdgcn_sched_barrier(0);
-                    lds_wait<young>(bv1[kk]);
-                    mfma32_v(pacc[1], ad[kk], bv1[kk]);
+                    mfma_v<-1>(pacc[1], ad[kk], bv1[kk]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                static_for<0, EPM>([&](auto E) { exp_elem(std::integral_constant<int, (2 * (NS + kk) + 1) * EPM + decltype(E)::value>{}); });
+                exp_chunk(std::integral_constant<int, 2 * (NS + kk) + 1>{});
             } else {
                 // ---- dV(u), dS products ----
                 constexpr int t = s - 3 * NS, c = t / NDB, db = t % NDB;
-                lds_wait<young>(bd0[t], bd1[t]);
+                if constexpr (even) lds_wait4<W>(bd0[t], bd1[t], bd0[t + 1], bd1[t + 1]);
                 const u32x4 bdo = {bd0[t][0], bd0[t][1], bd1[t][0], bd1[t][1]};
-                dvacc[0][db] = mfma32(as_bf16x8(pp[0][c]), as_bf16x8(bdo), dvacc[0][db]);
+                mfma_a(dvacc[0][db], pp[0][c], bdo);
                 __builtin_amdgcn_sched_barrier(0);
-                if constexpr (t == 0) results_ready2(pacc[0], pacc[1]);
+                if constexpr (t == 0) {
+                    static_for<((4 * NS - 1) * EPM) / 2, 16>([&](auto J) { pack_pair(J); });  // the last pair(s) of P
+                    results_ready2(pacc[0], pacc[1]);
+                }
                 static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
-                dvacc[1][db] = mfma32(as_bf16x8(pp[1][c]), as_bf16x8(bdo), dvacc[1][db]);
+                mfma_a(dvacc[1][db], pp[1][c], bdo);
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
             }
         });
         __builtin_amdgcn_sched_barrier(0);
         --steps_left;
-        if (steps_left > 0) advance(cc);
-        if (d_left > 0) { advance(dc); --d_left; }
+        if (steps_left > 0) cur_it = (cur_it == it_begin) ? it_end - 1 : cur_it - 1;
+        advance_load();
     };
 
     // Four steps per iteration, one per ring position; the step count is rounded up to a multiple of four
