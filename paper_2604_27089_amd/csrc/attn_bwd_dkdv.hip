@@ -272,11 +272,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         return (s >= 2 * NS && s < 3 * NS) ? 3 : 4;
     };
     constexpr int kMaxAhead = 4;
-    // reads issued after those of slot s+1 by the time (even) slot s waits (none for the next body if `last`)
+    // reads issued after those of slot s+1 by the time (even) slot s waits, which is before slot s issues
+    // its own (none for the next body if `last`)
     auto young_reads = [=](int s, bool last) constexpr {
         int n = 0;
         for (int x = s + 2; x <= s + kMaxAhead; ++x)
-            if (x - ahead(x) <= s && !(last && x >= P4)) n += nreads(x);
+            if (x - ahead(x) <= s - 1 && !(last && x >= P4)) n += nreads(x);
         return n;
     };
 
@@ -364,14 +365,18 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 vmem_wait<GROUP>();
                 __builtin_amdgcn_s_barrier();
             }
-            static_for<1, kMaxAhead + 1>([&](auto AC) {
-                constexpr int x = s + decltype(AC)::value;
-                if constexpr (x - ahead(x) == s) {
-                    if constexpr (x < P4) issue_reads(BUFC, std::integral_constant<int, x>{});
-                    else if constexpr (!LAST) issue_reads(NextBuf{}, std::integral_constant<int, x - P4>{});
-                }
-            });
-            __builtin_amdgcn_sched_barrier(0);
+            // the reads this slot issues go out behind its first MFMA (a read holds the wave's issue for
+            // about half an MFMA; in front of the MFMA that time would be lost)
+            auto issue_slot = [&]() __attribute__((always_inline)) {
+                static_for<1, kMaxAhead + 1>([&](auto AC) {
+                    constexpr int x = s + decltype(AC)::value;
+                    if constexpr (x - ahead(x) == s) {
+                        if constexpr (x < P4) issue_reads(BUFC, std::integral_constant<int, x>{});
+                        else if constexpr (!LAST) issue_reads(NextBuf{}, std::integral_constant<int, x - P4>{});
+                    }
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            };
             if constexpr (s < NS) {
                 // ---- S(u); the loads of step u+2 ----
                 if constexpr (s == 0) {
@@ -380,12 +385,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                     seeds_to_acc(seed, sds);
                     mfma_vc(sacc[0], aq[s], kreg[0][s], seed);
                     __builtin_amdgcn_sched_barrier(0);
+                    issue_slot();
                     issue_load(std::integral_constant<int, 0>{}, DBUF);
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_vc(sacc[1], aq[s], kreg[1][s], seed);
                 } else {
                     mfma_v<W>(sacc[0], aq[s], kreg[0][s]);
                     __builtin_amdgcn_sched_barrier(0);
+                    issue_slot();
                     if constexpr (s < GROUP) issue_load(std::integral_constant<int, s>{}, DBUF);
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_v<-1>(sacc[1], aq[s], kreg[1][s]);
@@ -397,6 +404,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 const u32x4 bqt = {bq0[t][0], bq0[t][1], bq1[t][0], bq1[t][1]};
                 mfma_a(dkacc[0][db], dsp[0][c], bqt);
                 __builtin_amdgcn_sched_barrier(0);
+                issue_slot();
                 if constexpr (t == 0) {
                     results_ready2(sacc[0], sacc[1]);
                     // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
@@ -431,12 +439,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                     seeds_to_acc(seed, sdp);
                     mfma_vc(pacc[0], ad[kk], bv0[kk], seed);
                     __builtin_amdgcn_sched_barrier(0);
+                    issue_slot();
                     exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_vc(pacc[1], ad[kk], bv1[kk], seed);
                 } else {
                     mfma_v<W>(pacc[0], ad[kk], bv0[kk]);
                     __builtin_amdgcn_sched_barrier(0);
+                    issue_slot();
                     exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_v<-1>(pacc[1], ad[kk], bv1[kk]);
@@ -450,6 +460,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 const u32x4 bdo = {bd0[t][0], bd0[t][1], bd1[t][0], bd1[t][1]};
                 mfma_a(dvacc[0][db], pp[0][c], bdo);
                 __builtin_amdgcn_sched_barrier(0);
+                issue_slot();
                 if constexpr (t == 0) {
                     static_for<((4 * NS - 1) * EPM) / 2, 16>([&](auto J) { pack_pair(J); });  // the last pair(s) of P
                     results_ready2(pacc[0], pacc[1]);
