@@ -55,50 +55,6 @@ struct DkdvParams {
     float scale, scale_log2;
 };
 
-__device__ __forceinline__ void results_ready2(f32x16& a, f32x16& b) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
-}
-template <int N>
-__device__ __forceinline__ void vmem_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
-// Waits that tie the values they cover: used where the awaited registers are then combined into wider
-// operands (the combination must not be scheduled before the wait).
-template <int N>
-__device__ __forceinline__ void lds_wait4(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void lds_wait4(u32x2& a, u32x2& b, u32x2& c, u32x2& d) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
-}
-
-// MFMAs as assembly.  The kernel is bound by how many instructions a lone wave can issue, so these carry
-// no padding: the callers guarantee that no vector-ALU instruction writes an operand within the two
-// instructions before (operands come from LDS reads, from earlier MFMAs or from arithmetic done at least
-// one slot earlier), and results are read by the vector ALU only after results_ready2.  Volatile
-// assembly statements keep their order, which is what orders an MFMA after the wait that covers its
-// operands.  W: the wait for the operands rides in the same statement.
-//   _v: accumulator in vector registers; _vc: ... starting from another tile; _a: in accumulation registers
-template <int W>
-__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-template <int W>
-__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const u32x4& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
-}
-__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
-}
-__device__ __forceinline__ void mfma_a(f32x16& acc, const u32x4& a, const u32x4& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
 // 16 accumulator registers from the four 16-byte per-row reads of one lane
 __device__ __forceinline__ void seeds_to_acc(f32x16& acc, const u32x4 (&s)[4]) {
 #pragma unroll

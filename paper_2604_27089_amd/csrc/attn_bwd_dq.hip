@@ -6,18 +6,28 @@
 //   P_ij = exp(scale * q_i.k_j - LSE_i)
 //
 // One workgroup = 4 waves = 256 query rows of one query head, one wave per SIMD;
-// a wave owns 64 rows (two 32-row blocks): their Q and dO stay in registers as
-// MFMA B operands and their dQ lives in accumulator registers that only MFMAs
-// touch.  K/V tiles of 64 keys stream through LDS (direct global->LDS loads,
-// double-buffered, XOR-swizzled); every operand fetched from LDS feeds two
-// MFMAs, one per row block.  Per 32-key step and wave:
-//   S^T = K.Q^T, dP^T = V.dO^T          (keys on the register axis, one query per
-//        lane, so LSE and Delta are per-lane scalars; accumulators pinned to
-//        vector registers where the arithmetic reads them)
-//   dS = exp2(S*scale*log2e - LSE*log2e) * (dP - Delta)   (fp32 VALU, then bf16)
-//   dQ^T += K^T.dS^T                    (K^T from transposing LDS reads; the dS^T
-//        accumulator tile is already a valid B operand)
-// All LDS operand reads are asynchronous with explicit partial waits.
+// a wave owns 64 rows (two 32-row blocks): their Q and dO stay resident as MFMA
+// B operands (in accumulation registers), their dQ lives in accumulation
+// registers that only MFMAs touch, and -LSE/scale and -Delta of the lane's row
+// sit in register tiles that seed the S and dP accumulators through the MFMA C
+// operand.  K/V stream through rings of eight 32-key LDS tiles (direct
+// global->LDS loads issued six steps ahead, XOR-swizzled); every operand
+// fetched from LDS feeds two MFMAs, one per row block.  Per 32-key step u:
+//   S'^T = K.Q^T - LSE/scale, dP'^T = V.dO^T - Delta   (keys on the register axis,
+//        one query per lane)
+//   P = exp2(S' * scale*log2e), dS = P * dP'            (fp32 vector ALU, then bf16)
+//   dQ^T += K^T.dS^T                                    (K^T from transposing LDS reads;
+//        the dS^T accumulator tile is already a valid B operand)
+//
+// A lone wave issues in order, so the vector-ALU work is interleaved by hand
+// into the MFMA stream.  One loop body runs three phases of D/16 operand slots
+// (two MFMAs per slot):
+//   S(u) + the loads of step u+6 | dP(u) + exponentials | dQ(u-1) + dS products
+// i.e. the dQ contraction of a step is deferred into the next body.  The body is
+// straight-line code: LDS operand reads are asynchronous, issued four slots
+// ahead (across bodies) with one exact partial wait per pair of slots, and the
+// body is instantiated once per ring position so that LDS addresses are
+// immediates.
 #include "attn_common.h"
 #include "sp_common.h"
 
@@ -29,7 +39,9 @@ constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 constexpr int RPW = 64;           // query rows per wave
 constexpr int BM = RPW * kWaves;  // query rows per workgroup
-constexpr int BN = 64;            // keys per streamed tile (two 32-key steps)
+constexpr int BN = 32;            // keys per streamed tile = one step
+constexpr int NBUF = 8;           // ring of streamed tiles (K and V each)
+constexpr int LEAD = 6;           // a tile is loaded this many steps before its step
 
 struct DqParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* dO;
@@ -42,11 +54,13 @@ struct DqParams {
 
 template <int D, bool VARLEN>
 __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
-    constexpr int TILE = BN * D;
-    constexpr int NKK = D / 16;
-    constexpr int NDB = D / 32;
-    __shared__ __attribute__((aligned(1024))) __bf16 ks[2 * TILE];
-    __shared__ __attribute__((aligned(1024))) __bf16 vs[2 * TILE];
+    constexpr int NS = D / 16;   // operand slots per phase (contraction steps over the head dim)
+    constexpr int NDB = D / 32;  // 32-wide blocks of the head dim
+    constexpr int TILE_B = BN * D * 2;
+    constexpr int HALF_B = 16 * D * 2;  // 16 rows of a tile
+    constexpr int KS = 0, VS = NBUF * TILE_B, SMEM = 2 * NBUF * TILE_B;
+    static_assert(KS + (NBUF - 1) * TILE_B + HALF_B < 65536, "immediate LDS offsets must fit 16 bits");
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
     const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -58,38 +72,32 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
     const __bf16* qb_ = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + h) * D;
-    const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
-    const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
 
     const int i0 = qt * BM;
     const int wrow0 = i0 + RPW * wave;  // first row of this wave
 
-    bf16x8 qreg[2][NKK], doreg[2][NKK];
-    int qrow[2], row_lo[2];
-    float lse2[2], delta[2];
+    // resident B operands (Q^T, dO^T columns of this lane's two rows) and accumulator seeds
+    bf16x8 qreg[2][NS], doreg[2][NS];
+    f32x16 seed_s[2], seed_p[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        qrow[qb] = wrow0 + 32 * qb + lo;
-        const int rc = qrow[qb] < S ? qrow[qb] : S - 1;
+        const int row = wrow0 + 32 * qb + lo;
+        const int rc = row < S ? row : S - 1;
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
+        for (int kk = 0; kk < NS; ++kk) {
             qreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qb_ + (size_t)rc * q_row_stride + 16 * kk + 8 * hi));
             doreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(dob + (size_t)rc * q_row_stride + 16 * kk + 8 * hi));
         }
-        lse2[qb] = p.lse[((size_t)b * p.Hq + h) * S + rc] * kLog2e;
-        delta[qb] = p.delta[((size_t)b * p.Hq + h) * S + rc];
-        row_lo[qb] = VARLEN ? p.row_lo[rc] : 0;
+        const float ls = -p.lse[((size_t)b * p.Hq + h) * S + rc] / p.scale;
+        const float dl = -p.delta[((size_t)b * p.Hq + h) * S + rc];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { seed_s[qb][r] = ls; seed_p[qb][r] = dl; }
     }
-    int wave_lo_min = 0, wave_lo_max = 0, wg_lo_min = 0;
+    int wave_lo_max = 0, wg_lo_min = 0;
     if (VARLEN) {
-        wave_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[wrow0 < S ? wrow0 : S - 1]);
         wave_lo_max = __builtin_amdgcn_readfirstlane(p.row_lo[(wrow0 + RPW - 1 < S ? wrow0 + RPW - 1 : S - 1)]);
         wg_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[i0]);
     }
-    const int wave_q_min = wrow0, wave_q_max = wrow0 + RPW - 1;
-    const int jt_begin = VARLEN ? wg_lo_min / BN : 0;
-    const int last_row = (i0 + BM - 1 < S ? i0 + BM - 1 : S - 1);
-    const int jt_end = last_row / BN + 1;  // exclusive
 
     f32x16 dqacc[2][NDB];
 #pragma unroll
@@ -99,128 +107,272 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) dqacc[qb][db][r] = 0.f;
 
-    int roff[NKK];  // row-major operand (K, V rows): row lo (+32 per step), chunk 2*kk + hi
+    // LDS addresses of this lane's operand reads; everything that changes per step is an immediate
+    const uint32_t sm = lds_addr(smem);
+    uint32_t rk[NS], rv[NS];  // row-major operand (K, V rows): row lo, chunk 2*kk + hi
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) roff[kk] = tile_off_b128<D>(lo, 2 * kk + hi);
-    int toff[2][NDB];  // K^T operand: rows 16*c + 8*half + 4*hi + (0..3), cols 32*db + 16*(lo/16) + lo%16
+    for (int kk = 0; kk < NS; ++kk) {
+        rk[kk] = sm + tile_off_b128<D>(lo, 2 * kk + hi);
+        rv[kk] = rk[kk] + VS;
+    }
+    uint32_t tb[2][NDB];  // K^T operand: rows 8*half + 4*hi + (0..3) (+16 per 16-key half), cols 32*db + ...
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
-            toff[half][db] = tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
+            tb[half][db] = sm + tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
 
-    TileDma<D, BN, kWaves> dma;
-    dma.init(wave, lane, kv_row_stride);
+    const int jt_begin = VARLEN ? wg_lo_min / BN : 0;
+    const int last_row = (i0 + BM - 1 < S ? i0 + BM - 1 : S - 1);
+    const int jt_end = last_row / BN + 1;  // exclusive
+    const int total = jt_end - jt_begin;   // steps = key tiles, ascending
 
-    // one 32-key step: keys j0 .. j0+31 = rows 32*nb.. of the tile in buffer `buf`
-    auto step32 = [&](int buf, int nb, int j0) __attribute__((always_inline)) {
-        bool active = j0 <= wave_q_max;
-        if (VARLEN) active = active && (j0 + 32 > wave_lo_min);
-        if (!active) return;
-        const uint32_t ka = lds_addr(ks + buf * TILE) + nb * (32 * D * 2);
-        const uint32_t va = lds_addr(vs + buf * TILE) + nb * (32 * D * 2);
-
-        // ---- stage 1: S^T and dP^T for both row blocks ----
-        u32x4 ak[NKK], av[NKK];
-        constexpr int kAhead = 2;
-        auto load1 = [&](auto KK) __attribute__((always_inline)) {
-            constexpr int kk = decltype(KK)::value;
-            ak[kk] = lds_async_b128<0>(ka + roff[kk]);
-            av[kk] = lds_async_b128<0>(va + roff[kk]);
-        };
-        static_for<0, kAhead>([&](auto I) { load1(I); });
-        f32x16 sacc[2], pacc[2];
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<0, NKK>([&](auto KK) {
-            constexpr int kk = decltype(KK)::value;
-            if constexpr (kk + kAhead < NKK) load1(std::integral_constant<int, kk + kAhead>{});
-            constexpr int m2 = 2 * ((kk + kAhead < NKK ? kAhead : NKK - 1 - kk));  // reads of later groups in flight
-            lds_wait<m2 + 1>(ak[kk]);
-            if constexpr (kk == 0) {
-                mfma32_v0(sacc[0], ak[kk], qreg[0][kk]);
-                mfma32_v0(sacc[1], ak[kk], qreg[1][kk]);
-            } else {
-                mfma32_v(sacc[0], ak[kk], qreg[0][kk]);
-                mfma32_v(sacc[1], ak[kk], qreg[1][kk]);
-            }
-            lds_wait<m2>(av[kk]);
-            if constexpr (kk == 0) {
-                mfma32_v0(pacc[0], av[kk], doreg[0][kk]);
-                mfma32_v0(pacc[1], av[kk], doreg[1][kk]);
-            } else {
-                mfma32_v(pacc[0], av[kk], doreg[0][kk]);
-                mfma32_v(pacc[1], av[kk], doreg[1][kk]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        mfma_results_ready(sacc[0], sacc[1], pacc[0], pacc[1]);
-
-        // ---- stage 2: dS = P (dP - Delta) ----
-        bool need_mask = j0 + 31 > wave_q_min;
-        if (VARLEN) need_mask = need_mask || (j0 < wave_lo_max);
-        u32x4 dsp[2][2];  // bf16 B operands: [row block][16-key step]
+    // ---- global -> LDS loads of a step: K rows (PW), V rows (PW) per wave ----
+    using Dma = TileDma<D, BN, kWaves>;
+    constexpr int PW = Dma::PER_WAVE;
+    constexpr int GROUP = 2 * PW;
+    static_assert(GROUP <= NS, "one load per slot of the S phase");
+    const uint32_t stride_b = (uint32_t)(kv_row_stride * 2);
+    // byte offset, from the tile's first row, of the 16 bytes this lane fetches in its K-th load; rows past
+    // `lim` (tile-relative) re-read row `lim` (they are never used unmasked)
+    auto lane_off = [&](int K, int lim) __attribute__((always_inline)) {
+        const int row = Dma::RPI * (wave + kWaves * K) + lane / Dma::CH;
+        const uint32_t chunk_b = (uint32_t)(((lane % Dma::CH) ^ swz<D>(row)) * 16);
+        return (uint32_t)(row < lim ? row : lim) * stride_b + chunk_b;
+    };
+    uint32_t voff[PW];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float p0 = __builtin_amdgcn_exp2f(sacc[qb][r] * p.scale_log2 - lse2[qb]);
-                float p1 = __builtin_amdgcn_exp2f(sacc[qb][r + 1] * p.scale_log2 - lse2[qb]);
-                if (need_mask) {
-                    const int key0 = j0 + 8 * (r / 4) + 4 * hi + (r % 4);
-                    bool v0 = key0 <= qrow[qb], v1 = key0 + 1 <= qrow[qb];
-                    if (VARLEN) { v0 = v0 && key0 >= row_lo[qb]; v1 = v1 && key0 + 1 >= row_lo[qb]; }
-                    p0 = v0 ? p0 : 0.f;
-                    p1 = v1 ? p1 : 0.f;
-                }
-                const float d0 = p0 * (pacc[qb][r] - delta[qb]), d1 = p1 * (pacc[qb][r + 1] - delta[qb]);
-                dsp[qb][r / 8][(r % 8) / 2] = pack_bf16(d0, d1);
-            }
+    for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, BN - 1);
+    const int jt_tail = (S % BN != 0) ? (S - 1) / BN : -1;  // the tile that runs past the last row, if any
+
+    // the step being loaded: scalar byte pointers to its tile in k and v
+    struct LoadCursor { const char* k; const char* v; int jt, left; };
+    LoadCursor dc;
+    {
+        const size_t head0 = ((size_t)b * S * p.Hkv + g) * D * 2;
+        dc.jt = jt_begin;
+        dc.k = reinterpret_cast<const char*>(p.k) + head0 + (size_t)dc.jt * BN * stride_b;
+        dc.v = reinterpret_cast<const char*>(p.v) + head0 + (size_t)dc.jt * BN * stride_b;
+        dc.left = total - 1;
+    }
+    const size_t tile_step_b = (size_t)BN * stride_b;
+    auto advance_load = [&]() __attribute__((always_inline)) {
+        if (dc.left > 0) {  // past the last step the cursor stays (the padding steps re-read the last tile)
+            --dc.left; dc.jt += 1; dc.k += tile_step_b; dc.v += tile_step_b;
         }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- stage 3: dQ^T += K^T . dS^T ----
-        constexpr int N3 = 2 * NDB;  // (16-key step c, d block db)
-        constexpr int kAhead3 = 2;
-        u32x2 t0[N3], t1[N3];
-        auto load3 = [&](auto T) __attribute__((always_inline)) {
-            constexpr int t = decltype(T)::value, c = t / NDB, db = t % NDB;
-            t0[t] = lds_async_tr16<c * (16 * D * 2)>(ka + toff[0][db]);
-            t1[t] = lds_async_tr16<c * (16 * D * 2)>(ka + toff[1][db]);
-        };
-        static_for<0, kAhead3>([&](auto T) { load3(T); });
-        static_for<0, N3>([&](auto T) {
-            constexpr int t = decltype(T)::value, c = t / NDB, db = t % NDB;
-            if constexpr (t + kAhead3 < N3) load3(std::integral_constant<int, t + kAhead3>{});
-            constexpr int ahead = (t + kAhead3 < N3 ? kAhead3 : N3 - 1 - t);
-            lds_wait<2 * ahead>(t0[t], t1[t]);
-            const u32x4 kt = {t0[t][0], t0[t][1], t1[t][0], t1[t][1]};
-            dqacc[0][db] = mfma32(as_bf16x8(kt), as_bf16x8(dsp[0][c]), dqacc[0][db]);
-            dqacc[1][db] = mfma32(as_bf16x8(kt), as_bf16x8(dsp[1][c]), dqacc[1][db]);
-            __builtin_amdgcn_sched_barrier(0);
-        });
+    };
+    auto issue_load = [&](auto KC, int buf) __attribute__((always_inline)) {
+        constexpr int K = decltype(KC)::value, KK = K % PW;
+        uint32_t off = voff[KK];
+        if (dc.jt == jt_tail) off = lane_off(KK, S - 1 - dc.jt * BN);  // rare
+        const char* src = K < PW ? dc.k : dc.v;
+        char* dst = smem + (K < PW ? KS : VS) + buf * TILE_B + (wave + kWaves * KK) * 1024;
+        dma16(src + off, dst);
     };
 
-    if (jt_begin < jt_end) {
-        dma.issue(kb, jt_begin * BN, S - 1, ks, wave);
-        dma.issue(vb, jt_begin * BN, S - 1, vs, wave);
+    // ---- prologue: the first LEAD steps' tiles, and a finite stand-in for the deferred dQ of "step -1" ----
+    int cur_jt = jt_begin;   // key tile of the step being computed
+    int steps_left = total;  // real steps not yet computed (the count is padded to a multiple of NBUF)
+    {
+        static_for<0, PW>([&](auto K) { issue_load(K, NBUF - 1); });  // K rows of step 0 again, as the stand-in
+        static_for<0, LEAD>([&](auto T) {
+            static_for<0, GROUP>([&](auto K) { issue_load(K, decltype(T)::value); });
+            advance_load();
+        });
     }
-    for (int jt = jt_begin; jt < jt_end; ++jt) {
-        const int buf = (jt - jt_begin) & 1;
-        wait_vmem();      // this wave's share of tile jt is in LDS
-        __syncthreads();  // ... and everybody else's; everybody is done reading the other buffer
-        if (jt + 1 < jt_end) {
-            dma.issue(kb, (jt + 1) * BN, S - 1, ks + (buf ^ 1) * TILE, wave);
-            dma.issue(vb, (jt + 1) * BN, S - 1, vs + (buf ^ 1) * TILE, wave);
+
+    f32x16 sacc[2], pacc[2];
+    u32x4 dsp[2][2][2];  // bf16 B operands [parity of the step][row block][16-key half]
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) dsp[par][qb][c] = u32x4{0, 0, 0, 0};
+
+    // The operand slots of a body, x = 0 .. 3*NS-1 in the phases S | dP | dQ.  Reads of slot x are issued
+    // kAhead slots early (behind the first MFMA of the issuing slot), possibly from the previous body (slots
+    // x >= 3*NS name slots of the next body).  Waits happen once per pair of slots, at the even one.
+    constexpr int P3 = 3 * NS;
+    constexpr int kAhead = 4;
+    auto nreads = [](int x) constexpr { return (x % P3) < 2 * NS ? 1 : 2; };
+    // reads issued after those of slot s+1 by the time (even) slot s waits, which is before slot s issues
+    // its own (none for the next body if `last`)
+    auto young_reads = [=](int s, bool last) constexpr {
+        int n = 0;
+        for (int x = s + 2; x <= s - 1 + kAhead; ++x)
+            if (!(last && x >= P3)) n += nreads(x);
+        return n;
+    };
+
+    // in-flight operands (asynchronous reads: see the rule in attn_common.h)
+    u32x4 ak[NS], av[NS];
+    u32x2 t0[NS], t1[NS];
+
+    // reads of slot s (0 .. 3*NS-1) of the body at ring position BUF
+    auto issue_reads = [&](auto BUFC, auto SC) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(BUFC)::value, PBUF = (BUF + NBUF - 1) % NBUF, s = decltype(SC)::value;
+        if constexpr (s < NS) {
+            ak[s] = lds_async_b128<KS + BUF * TILE_B>(rk[s]);
+        } else if constexpr (s < 2 * NS) {
+            av[s - NS] = lds_async_b128<BUF * TILE_B>(rv[s - NS]);
+        } else {
+            constexpr int t = s - 2 * NS, c = t / NDB, db = t % NDB;
+            t0[t] = lds_async_tr16<KS + PBUF * TILE_B + c * HALF_B>(tb[0][db]);
+            t1[t] = lds_async_tr16<KS + PBUF * TILE_B + c * HALF_B>(tb[1][db]);
         }
-        step32(buf, 0, jt * BN);
-        step32(buf, 1, jt * BN + 32);
+    };
+
+    // One body = step u at ring position BUF: (BUF-1)%8 holds step u-1 (its dQ is done here), (BUF+6)%8
+    // receives step u+6.  FIRST: nothing was prefetched for this body (it follows the loop back-edge, which
+    // asynchronous values must not cross); LAST: it prefetches nothing for the next body.  In the very
+    // first body the deferred dQ multiplies the stand-in tile by zeros.
+    auto body = [&](auto BUFC, auto FIRSTC, auto LASTC) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(BUFC)::value, DBUF = (BUF + LEAD) % NBUF, PAR = BUF % 2;
+        constexpr bool FIRST = decltype(FIRSTC)::value, LAST = decltype(LASTC)::value;
+        using NextBuf = std::integral_constant<int, (BUF + 1) % NBUF>;
+        constexpr int EPM = 32 / (2 * NS);  // exponentials per MFMA in the dP phase
+        constexpr int PPM = 16 / (2 * NS);  // dS pairs per MFMA in the dQ phase
+
+        // exponentials of accumulator elements m*EPM .. of the step (element i = row block i/16, register
+        // i%16); P stays in the S' registers
+        auto exp_chunk = [&](auto MC) __attribute__((always_inline)) {
+            constexpr int m = decltype(MC)::value;
+            float t[EPM];
+            static_for<0, EPM>([&](auto E) {
+                constexpr int i = m * EPM + decltype(E)::value;
+                t[decltype(E)::value] = sacc[i / 16][i % 16] * p.scale_log2;
+            });
+            static_for<0, EPM>([&](auto E) {
+                constexpr int i = m * EPM + decltype(E)::value;
+                sacc[i / 16][i % 16] = __builtin_amdgcn_exp2f(t[decltype(E)::value]);
+            });
+        };
+        // dS of the pair j (0..15), for the dQ of the next body
+        auto ds_pair = [&](auto JC) __attribute__((always_inline)) {
+            constexpr int j = decltype(JC)::value, qb = j / 8, r = 2 * (j % 8);
+            uint32_t w = pack_bf16(sacc[qb][r] * pacc[qb][r], sacc[qb][r + 1] * pacc[qb][r + 1]);
+            asm volatile("" : "+v"(w));  // pins the arithmetic here: its only consumers are in the next body
+            dsp[PAR][qb][r / 8][(r % 8) / 2] = w;
+        };
+
+        // Everybody is done with the previous body: nobody reads ring position (BUF+6)%8 = (BUF-2)%8 any
+        // more.  This wave's loads of step u+1 have landed (those of the four steps after it may be in
+        // flight); after the barrier so have everybody's.
+        vmem_wait<(LEAD - 2) * GROUP>();
+        __builtin_amdgcn_s_barrier();
+
+        if constexpr (FIRST) static_for<0, kAhead>([&](auto XC) { issue_reads(BUFC, XC); });
+        static_for<0, P3>([&](auto SC) {
+            constexpr int s = decltype(SC)::value;
+            constexpr bool even = s % 2 == 0;
+            constexpr int W = even ? young_reads(s, LAST) : -1;  // reads allowed to stay in flight at the pair's wait
+            __builtin_amdgcn_sched_barrier(0);
+            // the reads this slot issues go out behind its first MFMA
+            auto issue_slot = [&]() __attribute__((always_inline)) {
+                constexpr int x = s + kAhead;
+                if constexpr (x < P3) issue_reads(BUFC, std::integral_constant<int, x>{});
+                else if constexpr (!LAST) issue_reads(NextBuf{}, std::integral_constant<int, x - P3>{});
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            if constexpr (s < NS) {
+                // ---- S(u); the loads of step u+6 ----
+                if constexpr (s == 0) mfma_vc_ab<W>(sacc[0], ak[s], qreg[0][s], seed_s[0]);
+                else mfma_v_ab<W>(sacc[0], ak[s], qreg[0][s]);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_slot();
+                if constexpr (s < GROUP) issue_load(SC, DBUF);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (s == 0) mfma_vc_ab<-1>(sacc[1], ak[s], qreg[1][s], seed_s[1]);
+                else mfma_v_ab<-1>(sacc[1], ak[s], qreg[1][s]);
+            } else if constexpr (s < 2 * NS) {
+                // ---- dP(u), exponentials ----
+                constexpr int kk = s - NS;
+                if constexpr (kk == 0) mfma_vc_ab<W>(pacc[0], av[kk], doreg[0][kk], seed_p[0]);
+                else mfma_v_ab<W>(pacc[0], av[kk], doreg[0][kk]);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_slot();
+                if constexpr (kk == 0) {
+                    results_ready2(sacc[0], sacc[1]);
+                    // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
+                    const int j0 = cur_jt * BN;
+                    const bool real = steps_left > 0;
+                    if (!real || j0 + 31 > wrow0 || j0 < wave_lo_max) {  // rare
+                        asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb) {
+                            const int row = wrow0 + 32 * qb + (int)(__lane_id() & 31);
+                            const int rlo = VARLEN ? p.row_lo[row < S ? row : S - 1] : 0;  // first key the row may see
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int key = j0 + 8 * (r / 4) + 4 * (int)(__lane_id() >> 5) + (r % 4);
+                                const bool vis = real && key <= row && key >= rlo;
+                                sacc[qb][r] = vis ? sacc[qb][r] : -__builtin_inff();
+                            }
+                        }
+                    }
+                }
+                exp_chunk(std::integral_constant<int, 2 * kk>{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (kk == 0) mfma_vc_ab<-1>(pacc[1], av[kk], doreg[1][kk], seed_p[1]);
+                else mfma_v_ab<-1>(pacc[1], av[kk], doreg[1][kk]);
+                __builtin_amdgcn_sched_barrier(0);
+                exp_chunk(std::integral_constant<int, 2 * kk + 1>{});
+            } else {
+                // ---- dQ(u-1), dS products of step u ----
+                constexpr int t = s - 2 * NS, c = t / NDB, db = t % NDB;
+                if constexpr (even) lds_wait4<W>(t0[t], t1[t], t0[t + 1], t1[t + 1]);
+                const u32x4 kt = {t0[t][0], t0[t][1], t1[t][0], t1[t][1]};
+                mfma_a(dqacc[0][db], kt, dsp[1 - PAR][0][c]);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_slot();
+                if constexpr (t == 0) results_ready2(pacc[0], pacc[1]);
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_a(dqacc[1][db], kt, dsp[1 - PAR][1][c]);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
+            }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        --steps_left;
+        if (steps_left > 0) cur_jt += 1;
+        advance_load();
+    };
+
+    // Eight steps per iteration, one per ring position; the step count is rounded up to a multiple of
+    // eight with steps whose P is all zero (they re-read the last tile).
+    for (int u = 0; u < total; u += NBUF) {
+        body(std::integral_constant<int, 0>{}, std::true_type{}, std::false_type{});
+        body(std::integral_constant<int, 1>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 2>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 3>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 4>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 5>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 6>{}, std::false_type{}, std::false_type{});
+        body(std::integral_constant<int, 7>{}, std::false_type{}, std::true_type{});
     }
+
+    // ---- the deferred dQ of the last step (ring position 7, dS of parity 1) ----
+    {
+        static_for<0, NS>([&](auto TC) {
+            constexpr int t = decltype(TC)::value, c = t / NDB, db = t % NDB;
+            u32x2 h0 = lds_async_tr16<KS + (NBUF - 1) * TILE_B + c * HALF_B>(tb[0][db]);
+            u32x2 h1 = lds_async_tr16<KS + (NBUF - 1) * TILE_B + c * HALF_B>(tb[1][db]);
+            lds_wait<0>(h0, h1);
+            const u32x4 kt = {h0[0], h0[1], h1[0], h1[1]};
+            dqacc[0][db] = mfma32(as_bf16x8(kt), as_bf16x8(dsp[1][0][c]), dqacc[0][db]);
+            dqacc[1][db] = mfma32(as_bf16x8(kt), as_bf16x8(dsp[1][1][c]), dqacc[1][db]);
+        });
+    }
+    wait_vmem();  // no direct-to-LDS load may outlive the workgroup's LDS allocation
 
     // ---- write dQ (scaled): accumulator rows = d, column = this lane's query ----
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        if (qrow[qb] < S) {
-            __bf16* out = p.dq + (((size_t)b * S + qrow[qb]) * p.Hq + h) * D;
+        const int row = wrow0 + 32 * qb + lo;
+        if (row < S) {
+            __bf16* out = p.dq + (((size_t)b * S + row) * p.Hq + h) * D;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll

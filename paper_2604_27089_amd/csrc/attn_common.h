@@ -211,6 +211,68 @@ __device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16&
     asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
+// ---------------------------------------------------------------------------
+// Unpadded assembly MFMAs for the hand-scheduled backward kernels.
+//
+// Those kernels run one wave per SIMD and are bound by how many instructions
+// that lone wave can issue, so these helpers carry no padding.  The callers
+// guarantee that no vector-ALU instruction writes an operand within the two
+// instructions before the MFMA (operands come from LDS reads, from earlier
+// MFMAs, or from arithmetic done at least one operand slot earlier), and the
+// vector ALU reads MFMA results only after results_ready2.  Volatile assembly
+// statements keep their order, which is what orders an MFMA after the wait
+// that covers its operands.  W >= 0: that wait rides in the same statement.
+//   mfma_v  : accumulator in vector registers       mfma_vc : ... starting from another tile
+//   mfma_a  : accumulator in accumulation registers
+//   *_ab    : the B operand lives in accumulation registers (resident operands)
+// ---------------------------------------------------------------------------
+template <int W>
+__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+template <int W>
+__device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const u32x4& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma_a(f32x16& acc, const u32x4& a, const u32x4& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+template <int W>
+__device__ __forceinline__ void mfma_v_ab(f32x16& acc, const u32x4& a, const bf16x8& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+template <int W>
+__device__ __forceinline__ void mfma_vc_ab(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%4)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(c), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(c));
+}
+// MFMA results in vector registers may be read by other instructions after this
+__device__ __forceinline__ void results_ready2(f32x16& a, f32x16& b) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
+}
+// at most N of this wave's global loads (register and LDS destinations) are still in flight
+template <int N>
+__device__ __forceinline__ void vmem_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// Waits that tie the values they cover: used where the awaited registers are then combined into wider
+// operands (the combination must not be scheduled before the wait).
+template <int N>
+__device__ __forceinline__ void lds_wait4(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait4(u32x2& a, u32x2& b, u32x2& c, u32x2& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+
 // Per-lane description of the DMA loads that fill one ROWS x D tile with NW waves.
 // (NW waves).  Instruction i (0 .. ROWS*CH/64-1) covers 64/CH rows; wave w issues i = w, w+NW, ...
 // `wave` must be wave-uniform in the scalar sense (readfirstlane) so that LDS
