@@ -171,8 +171,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     };
 
     // ---- prologue: the first LEAD steps' tiles, and a finite stand-in for the deferred dQ of "step -1" ----
-    int cur_jt = jt_begin;   // key tile of the step being computed
-    int steps_left = total;  // real steps not yet computed (the count is padded to a multiple of NBUF)
+    int cur_jt = jt_begin;  // key tile of the step being computed
+    int step_no = 0;        // its number (the step count is padded to a multiple of NBUF: steps >= total are not real)
+    // steps whose S' needs masking: from the first whose keys reach past the wave's first row (and every
+    // padding step), and, for packed documents, those before the wave's last row's document starts
+    const int mask_from = (wrow0 / BN - jt_begin) < total ? (wrow0 / BN - jt_begin) : total;
+    const int mask_until = VARLEN ? (wave_lo_max + BN - 1) / BN - jt_begin : 0;
     {
         static_for<0, PW>([&](auto K) { issue_load(K, NBUF - 1); });  // K rows of step 0 again, as the stand-in
         static_for<0, LEAD>([&](auto T) {
@@ -287,18 +291,25 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
                 else mfma_v_ab<-1>(sacc[1], ak[s], qreg[1][s]);
             } else if constexpr (s < 2 * NS) {
                 // ---- dP(u), exponentials ----
+                // Exponential chunk m runs behind MFMA m+1 of the phase (the last one behind the first MFMA
+                // of the dQ phase): two MFMAs have then issued since the last write of S', which covers the
+                // wait states between an MFMA and a vector-ALU read of its result.
                 constexpr int kk = s - NS;
                 if constexpr (kk == 0) mfma_vc_ab<W>(pacc[0], av[kk], doreg[0][kk], seed_p[0]);
                 else mfma_v_ab<W>(pacc[0], av[kk], doreg[0][kk]);
                 __builtin_amdgcn_sched_barrier(0);
                 issue_slot();
+                if constexpr (kk > 0) exp_chunk(std::integral_constant<int, 2 * kk - 1>{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (kk == 0) mfma_vc_ab<-1>(pacc[1], av[kk], doreg[1][kk], seed_p[1]);
+                else mfma_v_ab<-1>(pacc[1], av[kk], doreg[1][kk]);
+                __builtin_amdgcn_sched_barrier(0);
                 if constexpr (kk == 0) {
-                    results_ready2(sacc[0], sacc[1]);
                     // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
-                    const int j0 = cur_jt * BN;
-                    const bool real = steps_left > 0;
-                    if (!real || j0 + 31 > wrow0 || j0 < wave_lo_max) {  // rare
+                    if (step_no >= mask_from || step_no < mask_until) {  // rare
                         asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
+                        const int j0 = cur_jt * BN;
+                        const bool real = step_no < total;
 #pragma unroll
                         for (int qb = 0; qb < 2; ++qb) {
                             const int row = wrow0 + 32 * qb + (int)(__lane_id() & 31);
@@ -313,30 +324,25 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
                     }
                 }
                 exp_chunk(std::integral_constant<int, 2 * kk>{});
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (kk == 0) mfma_vc_ab<-1>(pacc[1], av[kk], doreg[1][kk], seed_p[1]);
-                else mfma_v_ab<-1>(pacc[1], av[kk], doreg[1][kk]);
-                __builtin_amdgcn_sched_barrier(0);
-                exp_chunk(std::integral_constant<int, 2 * kk + 1>{});
             } else {
-                // ---- dQ(u-1), dS products of step u ----
+                // ---- dQ(u-1), dS products of step u (pair chunk m behind MFMA m+1, as above) ----
                 constexpr int t = s - 2 * NS, c = t / NDB, db = t % NDB;
-                if constexpr (even) lds_wait4<W>(t0[t], t1[t], t0[t + 1], t1[t + 1]);
                 const u32x4 kt = {t0[t][0], t0[t][1], t1[t][0], t1[t][1]};
-                mfma_a(dqacc[0][db], kt, dsp[1 - PAR][0][c]);
+                mfma_a_w<W>(dqacc[0][db], kt, dsp[1 - PAR][0][c]);
                 __builtin_amdgcn_sched_barrier(0);
                 issue_slot();
-                if constexpr (t == 0) results_ready2(pacc[0], pacc[1]);
-                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
+                if constexpr (t == 0) exp_chunk(std::integral_constant<int, 2 * NS - 1>{});
+                else static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t - 1) * PPM + decltype(J)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_a(dqacc[1][db], kt, dsp[1 - PAR][1][c]);
                 __builtin_amdgcn_sched_barrier(0);
-                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
+                if constexpr (t == NS - 1) static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
             }
         });
         __builtin_amdgcn_sched_barrier(0);
-        --steps_left;
-        if (steps_left > 0) cur_jt += 1;
+        ++step_no;
+        if (step_no < total) cur_jt += 1;
         advance_load();
     };
 

@@ -246,6 +246,11 @@ __device__ __forceinline__ void mfma_a(f32x16& acc, const u32x4& a, const u32x4&
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 template <int W>
+__device__ __forceinline__ void mfma_a_w(f32x16& acc, const u32x4& a, const u32x4& b) {
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+template <int W>
 __device__ __forceinline__ void mfma_v_ab(f32x16& acc, const u32x4& a, const bf16x8& b) {
     if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b), "n"(W));
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
