@@ -194,7 +194,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 
     // ---- prologue: V (resident), a finite stand-in tile for the deferred dK of "step -1", steps 0 and 1 ----
     int cur_it = it_end - 1;  // row tile of the step being computed
-    int steps_left = total;   // real steps not yet computed (the count is padded to a multiple of four)
+    int step_no = 0;          // its number (the step count is padded to a multiple of four: steps >= total are not real)
+    // row tiles whose S' needs masking: those reaching down into the wave's keys, and those reaching the end
+    // of the first key's document (dense: the end of the sequence)
+    const int it_mask_lo = (wkey0 + KPW - 2) / BMQ;
+    const int it_mask_hi = (wave_hi_min - 31 + BMQ - 1) / BMQ;
     {
         TileDma<D, BNK, kWaves> vdma;
         vdma.init(wave, lane, kv_row_stride);
@@ -355,19 +359,24 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 }
             } else if constexpr (s < 2 * NS) {
                 // ---- dK(u-1), exponentials of key block 0 ----
+                // Exponential chunk m runs behind MFMA m+1 of the dK and dP phases taken together (the last
+                // one behind the first MFMA of the dV phase): two MFMAs have then issued since the last write
+                // of S', which covers the wait states between an MFMA and a vector-ALU read of its result.
                 constexpr int t = s - NS, c = t / NDB, db = t % NDB;
-                if constexpr (even) lds_wait4<W>(bq0[t], bq1[t], bq0[t + 1], bq1[t + 1]);
                 const u32x4 bqt = {bq0[t][0], bq0[t][1], bq1[t][0], bq1[t][1]};
-                mfma_a(dkacc[0][db], dsp[0][c], bqt);
+                mfma_a_w<W>(dkacc[0][db], dsp[0][c], bqt);
                 __builtin_amdgcn_sched_barrier(0);
                 issue_slot();
+                if constexpr (t > 0) exp_chunk(std::integral_constant<int, 2 * t - 1>{});
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_a(dkacc[1][db], dsp[1][c], bqt);
+                __builtin_amdgcn_sched_barrier(0);
                 if constexpr (t == 0) {
-                    results_ready2(sacc[0], sacc[1]);
                     // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
-                    const int q0 = cur_it * BMQ;
-                    const bool real = steps_left > 0;
-                    if (!real || q0 < wkey0 + KPW - 1 || q0 + 31 >= wave_hi_min) {  // rare
+                    if (cur_it <= it_mask_lo || cur_it >= it_mask_hi || step_no >= total) {  // rare
                         asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
+                        const int q0 = cur_it * BMQ;
+                        const bool real = step_no < total;
 #pragma unroll
                         for (int kbk = 0; kbk < 2; ++kbk) {
                             const int key = wkey0 + 32 * kbk + (int)(__lane_id() & 31);
@@ -382,10 +391,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                     }
                 }
                 exp_chunk(std::integral_constant<int, 2 * t>{});
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_a(dkacc[1][db], dsp[1][c], bqt);
-                __builtin_amdgcn_sched_barrier(0);
-                exp_chunk(std::integral_constant<int, 2 * t + 1>{});
             } else if constexpr (s < 3 * NS) {
                 // ---- dP(u), exponentials of key block 1 ----
                 constexpr int kk = s - 2 * NS;
@@ -396,41 +401,42 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                     mfma_vc(pacc[0], ad[kk], bv0[kk], seed);
                     __builtin_amdgcn_sched_barrier(0);
                     issue_slot();
-                    exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
+                    exp_chunk(std::integral_constant<int, 2 * (NS + kk) - 1>{});
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_vc(pacc[1], ad[kk], bv1[kk], seed);
                 } else {
                     mfma_v<W>(pacc[0], ad[kk], bv0[kk]);
                     __builtin_amdgcn_sched_barrier(0);
                     issue_slot();
-                    exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
+                    exp_chunk(std::integral_constant<int, 2 * (NS + kk) - 1>{});
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_v<-1>(pacc[1], ad[kk], bv1[kk]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                exp_chunk(std::integral_constant<int, 2 * (NS + kk) + 1>{});
+                exp_chunk(std::integral_constant<int, 2 * (NS + kk)>{});
             } else {
-                // ---- dV(u), dS products ----
+                // ---- dV(u), dS products (pair chunk m behind MFMA m+1 of the phase, as above) ----
                 constexpr int t = s - 3 * NS, c = t / NDB, db = t % NDB;
-                if constexpr (even) lds_wait4<W>(bd0[t], bd1[t], bd0[t + 1], bd1[t + 1]);
                 const u32x4 bdo = {bd0[t][0], bd0[t][1], bd1[t][0], bd1[t][1]};
-                mfma_a(dvacc[0][db], pp[0][c], bdo);
+                mfma_a_w<W>(dvacc[0][db], pp[0][c], bdo);
                 __builtin_amdgcn_sched_barrier(0);
                 issue_slot();
                 if constexpr (t == 0) {
+                    exp_chunk(std::integral_constant<int, 4 * NS - 1>{});
                     static_for<((4 * NS - 1) * EPM) / 2, 16>([&](auto J) { pack_pair(J); });  // the last pair(s) of P
-                    results_ready2(pacc[0], pacc[1]);
+                } else {
+                    static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t - 1) * PPM + decltype(J)::value>{}); });
                 }
-                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_a(dvacc[1][db], pp[1][c], bdo);
                 __builtin_amdgcn_sched_barrier(0);
-                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
+                static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t) * PPM + decltype(J)::value>{}); });
+                if constexpr (t == NS - 1) static_for<0, PPM>([&](auto J) { ds_pair(std::integral_constant<int, (2 * t + 1) * PPM + decltype(J)::value>{}); });
             }
         });
         __builtin_amdgcn_sched_barrier(0);
-        --steps_left;
-        if (steps_left > 0) cur_it = (cur_it == it_begin) ? it_end - 1 : cur_it - 1;
+        ++step_no;
+        if (step_no < total) cur_it = (cur_it == it_begin) ? it_end - 1 : cur_it - 1;
         advance_load();
     };
 
