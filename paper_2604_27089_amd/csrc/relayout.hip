@@ -97,6 +97,35 @@ __global__ __launch_bounds__(kFastThreads) void relayout_pow2_kernel(const u32x4
         if (e0 + u * kFastThreads < slab_vec) __builtin_nontemporal_store(val[u], dst + to[u]);
 }
 
+// Unpack with linear stores: one workgroup writes kFastThreads*UNROLL consecutive vectors of the
+// sequence-side tensor and gathers them from the P slabs of the head-side tensor (runs and P powers of
+// two).  Stores are the slower direction of the memory system (a write-only stream reaches 5.6 TB/s on
+// MI355X, a read-only one 7.1), so for long runs the unpack keeps its stores contiguous and scatters its
+// loads instead: 5.7 against 5.3 TB/s on 2 KB runs; on 256-byte runs the slab-wise kernel above stays
+// ahead.  grid = (ceil(P*S_l*run / (kFastThreads*UNROLL)), B).
+template <int UNROLL>
+__global__ __launch_bounds__(kFastThreads) void unpack_pow2_linear_store_kernel(const u32x4* __restrict__ in,
+                                                                           u32x4* __restrict__ out,
+                                                                           uint32_t slab_vec, uint32_t log2_run,
+                                                                           uint32_t log2_P) {
+    const uint32_t b = blockIdx.y;
+    const uint32_t batch_vec = slab_vec << log2_P;
+    const u32x4* src = in + (size_t)b * batch_vec;
+    u32x4* dst = out + (size_t)b * batch_vec;
+    const uint32_t run_mask = (1u << log2_run) - 1u, p_mask = (1u << log2_P) - 1u;
+    const uint32_t o0 = blockIdx.x * (kFastThreads * UNROLL) + threadIdx.x;
+    u32x4 val[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t o = o0 + u * kFastThreads;  // vector of the sequence-side tensor: (s, p, r)
+        const uint32_t r = o & run_mask, sp_ = o >> log2_run, p = sp_ & p_mask, s = sp_ >> log2_P;
+        if (o < batch_vec) val[u] = __builtin_nontemporal_load(src + (size_t)(p * slab_vec + (s << log2_run) + r));
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+        if (o0 + u * kFastThreads < batch_vec) __builtin_nontemporal_store(val[u], dst + (o0 + u * kFastThreads));
+}
+
 }  // namespace
 
 namespace sp {
@@ -117,6 +146,18 @@ sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int
         while ((1ull << lr) < run) ++lr;
         const int unroll = run >= 64 ? 2 : 4;
         const uint64_t pb = (uint64_t)kFastThreads * unroll;
+        if (!to_head && (P & (P - 1)) == 0 && run >= 128) {  // measured: linear stores win from 2 KB runs on
+            uint32_t lp = 0;
+            while ((1 << lp) < P) ++lp;
+            dim3 g3((unsigned)((slab * (uint64_t)P + pb - 1) / pb), (unsigned)B);
+            if (unroll == 2)
+                hipLaunchKernelGGL((unpack_pow2_linear_store_kernel<2>), g3, dim3(kFastThreads), 0, st,
+                                   (const u32x4*)in, (u32x4*)out, (uint32_t)slab, lr, lp);
+            else
+                hipLaunchKernelGGL((unpack_pow2_linear_store_kernel<4>), g3, dim3(kFastThreads), 0, st,
+                                   (const u32x4*)in, (u32x4*)out, (uint32_t)slab, lr, lp);
+            return launch_status();
+        }
         dim3 g2((unsigned)((slab + pb - 1) / pb), (unsigned)P, (unsigned)B);
 #define SP_FAST(TH, U)                                                                                   \
     hipLaunchKernelGGL((relayout_pow2_kernel<TH, U>), g2, dim3(kFastThreads), 0, st, (const u32x4*)in,    \

@@ -19,6 +19,8 @@ CASES = [
     (1, 64, 4, 4, 4, 4),        # 4-byte elements, D*4 = 16 bytes
     (2, 77, 12, 32, 1, 4),      # P = 1 is the identity
     (1, 4096, 32, 128, 8, 2),   # 8B-shaped shard (config 2)
+    (2, 33, 16, 128, 2, 2),     # 2 KB runs (linear-store unpack path), ragged slab, batch > 1
+    (1, 5, 32, 128, 4, 4),      # 4 KB runs, fewer vectors than one block
 ]
 
 
