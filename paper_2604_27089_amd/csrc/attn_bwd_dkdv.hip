@@ -50,8 +50,9 @@ struct DkdvParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* dO;
     const float* aux;  // per 32-row tile: 32 x -LSE/scale then 32 x -Delta; [B*Hq, S_pad/32, 2, 32]
     __bf16* dk; __bf16* dv;
+    float* part;  // nsplit > 1: fp32 partial sums, [2 (dK unscaled, dV)][nsplit][B, S, Hkv, D]
     const int32_t* row_hi;
-    int32_t S, S_pad, Hq, Hkv, G, n_ktiles;
+    int32_t S, S_pad, Hq, Hkv, G, n_ktiles, nsplit;
     float scale, scale_log2;
 };
 
@@ -64,7 +65,7 @@ __device__ __forceinline__ void seeds_to_acc(f32x16& acc, const u32x4 (&s)[4]) {
     }
 }
 
-template <int D, bool VARLEN>
+template <int D, bool VARLEN, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     constexpr int NS = D / 16;   // operand slots per phase (contraction steps over the head dim)
     constexpr int NDB = D / 32;  // 32-wide blocks of the head dim
@@ -78,7 +79,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int jt = blockIdx.x;  // earliest key tiles (most rows to visit) first
+    // earliest key tiles (most rows to visit) first; the nsplit workgroups that share a key tile are neighbours
+    const int nsplit = SPLIT ? p.nsplit : 1;
+    const int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x, split = SPLIT ? blockIdx.x % nsplit : 0;
     const int g = blockIdx.y, b = blockIdx.z;
     const int S = p.S;
     const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
@@ -133,7 +136,17 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int it_begin = j0 / BMQ;                   // tile holding the first key's own row
     const int it_end = (wg_hi_max + BMQ - 1) / BMQ;  // exclusive
     const int n_it = it_end - it_begin;
-    const int total = n_it * p.G;  // steps: (head in group, row tile) pairs, rows descending
+    // Steps are (head in group, row tile) pairs, heads ascending, rows descending inside a head.  The
+    // key tile's step sequence is cut into nsplit contiguous chunks, one per workgroup; a chunk may be
+    // empty (its workgroup then contributes zeros).
+    const int total_all = n_it * p.G;
+    const int per_split = (total_all + nsplit - 1) / nsplit;
+    int s_begin = split * per_split < total_all ? split * per_split : total_all;
+    const int s_end = s_begin + per_split < total_all ? s_begin + per_split : total_all;
+    const int total = s_end - s_begin;
+    if (total == 0) s_begin = 0;  // keeps the prologue's loads on valid addresses
+    const int head_first = s_begin / n_it;             // first head (inside the group) of this chunk
+    const int it_first = it_end - 1 - s_begin % n_it;  // and its first row tile
 
     // ---- global -> LDS loads of a step: per-row scalars (1), Q rows (PW), dO rows (PW) per wave ----
     using Dma = TileDma<D, BMQ, kWaves>;
@@ -158,11 +171,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     struct LoadCursor { const char* q; const char* dO; const char* aux; int it, left; };
     LoadCursor dc;
     {
-        const size_t head0 = ((size_t)b * S * p.Hq + (size_t)g * p.G) * D * 2;
-        dc.it = it_end - 1;
+        const size_t head0 = ((size_t)b * S * p.Hq + (size_t)g * p.G + head_first) * D * 2;
+        dc.it = it_first;
         dc.q = reinterpret_cast<const char*>(p.q) + head0 + (size_t)dc.it * BMQ * stride_b;
         dc.dO = reinterpret_cast<const char*>(p.dO) + head0 + (size_t)dc.it * BMQ * stride_b;
-        dc.aux = reinterpret_cast<const char*>(p.aux) + (((size_t)b * p.Hq + (size_t)g * p.G) * (p.S_pad / 32) + dc.it) * 256;
+        dc.aux = reinterpret_cast<const char*>(p.aux) + (((size_t)b * p.Hq + (size_t)g * p.G + head_first) * (p.S_pad / 32) + dc.it) * 256;
         dc.left = total - 1;
     }
     const size_t tile_step_b = (size_t)BMQ * stride_b;
@@ -193,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     };
 
     // ---- prologue: V (resident), a finite stand-in tile for the deferred dK of "step -1", steps 0 and 1 ----
-    int cur_it = it_end - 1;  // row tile of the step being computed
+    int cur_it = it_first;    // row tile of the step being computed
     int step_no = 0;          // its number (the step count is padded to a multiple of four: steps >= total are not real)
     // row tiles whose S' needs masking: those reaching down into the wave's keys, and those reaching the end
     // of the first key's document (dense: the end of the sequence)
@@ -464,20 +477,58 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     }
     wait_vmem();  // no direct-to-LDS load may outlive the workgroup's LDS allocation
 
-    // ---- write dK (scaled) and dV: accumulator rows = keys, column = d ----
+    // ---- write dK and dV: accumulator rows = keys, column = d ----
+    if constexpr (SPLIT) {
+        // fp32 partial sums of this chunk (dK unscaled); the reduction kernel adds the chunks in a fixed order
+        const size_t n_out = (size_t)gridDim.z * S * p.Hkv * D;
+        float* pk = p.part + (size_t)split * n_out;
+        float* pv = pk + (size_t)nsplit * n_out;
 #pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
+        for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
-                if (krow < S) {
-                    const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
-                    p.dk[off] = (__bf16)(dkacc[kbk][db][r] * p.scale);
-                    p.dv[off] = (__bf16)dvacc[kbk][db][r];
+                for (int r = 0; r < 16; ++r) {
+                    const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
+                    if (krow < S) {
+                        const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
+                        pk[off] = dkacc[kbk][db][r];
+                        pv[off] = dvacc[kbk][db][r];
+                    }
                 }
-            }
+    } else {
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
+                    if (krow < S) {
+                        const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
+                        p.dk[off] = (__bf16)(dkacc[kbk][db][r] * p.scale);
+                        p.dv[off] = (__bf16)dvacc[kbk][db][r];
+                    }
+                }
+    }
+}
+
+// dK = scale * sum of the chunks' partial sums, dV = sum of theirs; four elements per thread
+__global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restrict__ part, __bf16* __restrict__ dk,
+                                                         __bf16* __restrict__ dv, int64_t n_out, int32_t nsplit,
+                                                         float scale) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n_out) return;  // n_out is a multiple of 4 (D is)
+    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int32_t s = 0; s < nsplit; ++s) {
+        sk += *reinterpret_cast<const f32x4*>(part + (size_t)s * n_out + i);
+        sv += *reinterpret_cast<const f32x4*>(part + ((size_t)nsplit + s) * n_out + i);
+    }
+    u32x2 wk, wv;
+    wk[0] = pack_bf16(sk[0] * scale, sk[1] * scale); wk[1] = pack_bf16(sk[2] * scale, sk[3] * scale);
+    wv[0] = pack_bf16(sv[0], sv[1]); wv[1] = pack_bf16(sv[2], sv[3]);
+    *reinterpret_cast<u32x2*>(dk + i) = wk;
+    *reinterpret_cast<u32x2*>(dv + i) = wv;
 }
 
 template <int D, bool VARLEN>
@@ -487,9 +538,19 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
     p.S = a.S; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.n_ktiles = (a.S + BNK - 1) / BNK;
+    p.nsplit = a.dkdv_splits; p.part = a.dkdv_part;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
-    dim3 grid(p.n_ktiles, a.Hkv, a.B);
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN>), grid, dim3(kThreads), 0, st, p);
+    if (p.nsplit < 1 || (p.nsplit > 1 && !p.part)) return SP_ERR_WORKSPACE;
+    dim3 grid(p.n_ktiles * p.nsplit, a.Hkv, a.B);
+    if (p.nsplit > 1) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN, false>), grid, dim3(kThreads), 0, st, p);
+    if (launch_status() != SP_OK) return SP_ERR_LAUNCH;
+    if (p.nsplit > 1) {
+        const int64_t n_out = (int64_t)a.B * a.S * a.Hkv * D;
+        const int64_t blocks = (n_out / 4 + 255) / 256;
+        hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p.part, p.dk, p.dv, n_out,
+                           p.nsplit, p.scale);
+    }
     return launch_status();
 }
 

@@ -33,7 +33,9 @@ inline float resolve_scale(float s, int32_t D) { return s > 0.f ? s : 1.0f / sqr
 
 // Workspace layout: [delta fp32 B*Hq*S] [per-row seeds fp32 2*B*Hq*S_pad: per 32-row tile, 32 x -LSE/scale
 // then 32 x -Delta] (bwd only)
-// [row_lo int32 T] [row_hi int32 T] (varlen only), each part rounded up to 256 bytes.
+// [row_lo int32 T] [row_hi int32 T] (varlen only)
+// [dK/dV partial sums fp32 2*nsplit*B*S*Hkv*D] (bwd only, when the dK/dV kernel splits its key tiles),
+// each part rounded up to 256 bytes.
 size_t delta_bytes(int64_t T, int32_t Hq) { return align_up((size_t)T * (size_t)Hq * sizeof(float), 256); }
 size_t bounds_bytes(int64_t T) { return align_up((size_t)T * sizeof(int32_t), 256); }
 size_t aux_bytes(int64_t B, int64_t S, int32_t Hq) {
@@ -80,6 +82,8 @@ size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_
     if (check_attn_shape(n_docs > 0 ? 1 : B, S_or_T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
     size_t n = delta_bytes(T, Hq) + 2 * aux_bytes(n_docs > 0 ? 1 : B, S_or_T, Hq);
     if (n_docs > 0) n += 2 * bounds_bytes(T);
+    const int64_t Bk = n_docs > 0 ? 1 : B;
+    n += align_up(sp::dkdv_part_bytes(Bk, S_or_T, Hkv, D, sp::dkdv_split_count(Bk, S_or_T, Hq, Hkv)), 256);
     return n < 256 ? 256 : n;
 }
 
@@ -138,6 +142,8 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = stages;
+    a.dkdv_splits = sp::dkdv_split_count(B, S, Hq, Hkv);
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
     return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
 }
 
@@ -201,6 +207,8 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
+    a.dkdv_splits = sp::dkdv_split_count(1, T, Hq, Hkv);
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)row_hi + bounds_bytes(T)) : nullptr;
     return sp::launch_attn_bwd(a, s);
 }
 

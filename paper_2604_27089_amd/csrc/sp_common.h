@@ -30,6 +30,8 @@ struct AttnArgs {
     int32_t B, S, Hq, Hkv, D;
     float scale;            // softmax scale (already defaulted)
     int32_t stages;         // bwd: bit mask of SP_BWD_STAGE_*
+    int32_t dkdv_splits;    // bwd: workgroups that share one key tile of the dK/dV kernel (dkdv_split_count)
+    float* dkdv_part;       // bwd workspace: their fp32 partial sums (null when dkdv_splits == 1)
 };
 
 sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int64_t H, int64_t D,
@@ -40,6 +42,27 @@ sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dq(const AttnArgs& a, hipStream_t st);
+
+// How many workgroups share one 256-key tile of the dK/dV kernel.  A key tile's work is every row from
+// its diagonal to the end of the sequence (or document), for every query head of the group: with one KV
+// head that is one workgroup per 256 keys, far too few to fill and balance 256 compute units below a
+// few hundred thousand rows (at 32K rows: 128 workgroups, the longest doing 1/64 of all the work).  The
+// (head, row tile) steps of a key tile are therefore cut into this many contiguous chunks, one workgroup
+// each, whose fp32 partial sums a second kernel adds in a fixed order.  About 2048 workgroups, at most 8
+// chunks (measured: 4.36 -> 1.65 ms at 32K rows, 10.1 -> 6.3 ms at 64K, 25.3 -> 24.7 ms at 128K).  The
+// count depends on the extents only, so packed documents and dense calls of equal extents agree bitwise.
+inline int32_t dkdv_split_count(int64_t B, int64_t S, int32_t Hq, int32_t Hkv) {
+    if (B <= 0 || S <= 0 || Hkv <= 0) return 1;
+    const int64_t tiles = (S + 255) / 256 * Hkv * B;
+    int64_t n = (2048 + tiles - 1) / tiles;
+    const int64_t steps_first = (S + 31) / 32 * (Hq / Hkv);  // steps of the longest key tile
+    if (n > steps_first / 32) n = steps_first / 32;            // chunks of at least 32 steps
+    if (n > 8) n = 8;
+    return n < 1 ? 1 : (int32_t)n;
+}
+inline size_t dkdv_part_bytes(int64_t B, int64_t S, int32_t Hkv, int32_t D, int32_t nsplit) {
+    return nsplit > 1 ? (size_t)2 * nsplit * B * S * Hkv * D * sizeof(float) : 0;
+}
 
 // row pitch of the per-row backward scalars
 inline int32_t aux_pitch(int64_t S) { return (int32_t)((S + 63) / 64 * 64 + 64); }

@@ -28,6 +28,7 @@ CASES = [
     ([1000], 2, 1, 128),                          # one document
     ([0, 0, 257, 0, 128, 128, 0], 2, 2, 64),      # leading/trailing empties, aligned docs
     ([700, 900, 333], 8, 2, 128),
+    ([2040, 8, 30, 2], 4, 1, 128),                # last key tile has fewer steps than workgroups sharing it
 ]
 
 
