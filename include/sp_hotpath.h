@@ -120,7 +120,9 @@ size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, in
  *   inputs : q, k, v, o (as written by the forward), lse, dO [B, S, Hq, D] bf16
  *   outputs: dq [B, S, Hq, D], dk, dv [B, S, Hkv, D]  bf16
  *   workspace: >= sp_attn_bwd_workspace_bytes(...) bytes, contents undefined
- *              on entry and exit (holds Delta_i = dO_i.O_i in fp32).
+ *              on entry and exit (holds Delta_i = dO_i.O_i in fp32, per-row
+ *              accumulator seeds, and fp32 partial sums of dK/dV when a key
+ *              tile's work is shared by several workgroups).
  *
  *   dV_j = sum_{a in group} sum_{i>=j} P_ij dO_i,  dP_ij = dO_i.v_j,
  *   dS_ij = P_ij (dP_ij - Delta_i),
@@ -145,6 +147,33 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
                              void* workspace, size_t workspace_bytes, int64_t B, int64_t S,
                              int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
                              int32_t stages, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * The same attention, forward and backward, on SEQUENCE-SIDE tensors: the pack
+ * of Q, K, V (and dO) and the unpack of O (and dQ, dK, dV) folded into the
+ * attention kernels' own loads and stores, so that no re-laid-out copy is ever
+ * written to memory (Section 2, Figure 1: the two layouts on either side of
+ * the exchange; on one device, what the exchange would move is read in place).
+ *
+ *   q, o, dO, dq [B, S_l, P*Hq, D]; k, v, dk, dv [B, S_l, P*Hkv, D]   bf16
+ *   lse [B, Hq, P*S_l]                                                 fp32
+ *
+ * Hq, Hkv are the per-peer head counts.  The result is, bit for bit,
+ *   unpack(sp_attn_fwd(pack(q), pack(k), pack(v)))  resp. the unpacked
+ * gradients of sp_attn_bwd on the packed tensors: attention row p*S_l + s,
+ * head j is sequence-side row s, head p*H + j.
+ * S_l must be a power of two >= 256 (no tile of any kernel may straddle two
+ * peers' chunks): SP_ERR_UNSUPPORTED otherwise.  Workspace of the backward:
+ * sp_attn_bwd_workspace_bytes(B, P*S_l, Hq, Hkv, D, 0).
+ * ------------------------------------------------------------------------- */
+sp_status sp_attn_fwd_seqlayout(const void* q, const void* k, const void* v, void* o, float* lse,
+                                int64_t B, int64_t S_l, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                                float softmax_scale, void* hip_stream);
+sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, const void* o,
+                                const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, int64_t B, int64_t S_l,
+                                int32_t Hq, int32_t Hkv, int32_t D, int32_t P, float softmax_scale,
+                                void* hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Packed variable-length documents (not in the paper; the block-diagonal form

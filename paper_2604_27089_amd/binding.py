@@ -23,7 +23,7 @@ SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_A
 EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
     "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
-    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd",
+    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
 )
 
 
@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_bwd.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, f32, vp]
     L.sp_attn_bwd_stages.restype = c.c_int
     L.sp_attn_bwd_stages.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, f32, i32, vp]
+    L.sp_attn_fwd_seqlayout.restype = c.c_int
+    L.sp_attn_fwd_seqlayout.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, f32, vp]
+    L.sp_attn_bwd_seqlayout.restype = c.c_int
+    L.sp_attn_bwd_seqlayout.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, i32, f32, vp]
     L.sp_attn_varlen_fwd.restype = c.c_int
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
@@ -166,6 +170,35 @@ def sp_attn_bwd_stages(q, k, v, o, lse, do, dq, dk, dv, workspace, stages: int, 
     _check(lib().sp_attn_bwd_stages(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
                                     _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
                                     float(softmax_scale), int(stages), _stream(stream)), "sp_attn_bwd_stages")
+    return dq, dk, dv
+
+
+def sp_attn_fwd_seqlayout(q, k, v, P: int, softmax_scale: float = 0.0, o=None, lse=None, stream=None):
+    """Sequence-side tensors q [B,S_l,P*Hq,D], k,v [B,S_l,P*Hkv,D] -> (o [B,S_l,P*Hq,D], lse [B,Hq,P*S_l])."""
+    B, S_l, PHq, D = q.shape
+    Hq, Hkv = PHq // P, k.shape[2] // P
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, Hq, P * S_l), dtype=torch.float32, device=q.device)
+    _check(lib().sp_attn_fwd_seqlayout(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, S_l, Hq, Hkv, D, P,
+                                       float(softmax_scale), _stream(stream)), "sp_attn_fwd_seqlayout")
+    return o, lse
+
+
+def sp_attn_bwd_seqlayout(q, k, v, o, lse, do, P: int, softmax_scale: float = 0.0, dq=None, dk=None, dv=None,
+                          workspace=None, stream=None):
+    """Backward on sequence-side tensors; returns (dq, dk, dv) shaped like q, k, v."""
+    B, S_l, PHq, D = q.shape
+    Hq, Hkv = PHq // P, k.shape[2] // P
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    if workspace is None:
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, P * S_l, Hq, Hkv, D, 0), q.device)
+    _check(lib().sp_attn_bwd_seqlayout(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
+                                       _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S_l, Hq, Hkv,
+                                       D, P, float(softmax_scale), _stream(stream)), "sp_attn_bwd_seqlayout")
     return dq, dk, dv
 
 

@@ -25,15 +25,17 @@ __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o
                                                    const float* __restrict__ lse,
                                                    float* __restrict__ delta, float* __restrict__ aux,
                                                    int32_t B, int32_t S, int32_t S_pad, int32_t Hq,
-                                                   float inv_scale) {
+                                                   float inv_scale, RowMap map) {
     constexpr int LPV = D / 8;  // lanes per (row, head) vector, 16 bytes each
     const int64_t n_vec = (int64_t)B * S * Hq;
     const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;
     const int part = threadIdx.x % LPV;
     float acc = 0.f;
     if (vec < n_vec) {
-        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(o + vec * D + 8 * part));
-        const bf16x8 b = as_bf16x8(*reinterpret_cast<const u32x4*>(dO + vec * D + 8 * part));
+        const int64_t bi_ = vec / Hq, b_ = bi_ / S;  // vec = (b*S + i)*Hq + h
+        const size_t at = (size_t)b_ * S * Hq * D + map.off((int32_t)(bi_ - b_ * S)) + (size_t)(vec - bi_ * Hq) * D + 8 * part;
+        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(o + at));
+        const bf16x8 b = as_bf16x8(*reinterpret_cast<const u32x4*>(dO + at));
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
     }
@@ -74,7 +76,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
         if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, st, (const __bf16*)a.o,
                            (const __bf16*)a.dO, a.lse, a.delta, a.aux, a.B, a.S, a.S_pad, a.Hq,
-                           1.0f / a.scale);
+                           1.0f / a.scale, a.qmap);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
         const int64_t npad = (int64_t)a.B * a.Hq * (a.S_pad - a.S);
         hipLaunchKernelGGL(aux_pad_kernel, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, st, a.aux, a.B * a.Hq,

@@ -52,6 +52,7 @@ struct DkdvParams {
     __bf16* dk; __bf16* dv;
     float* part;  // nsplit > 1: fp32 partial sums, [2 (dK unscaled, dV)][nsplit][B, S, Hkv, D]
     const int32_t* row_hi;
+    RowMap qmap, kvmap;
     int32_t S, S_pad, Hq, Hkv, G, n_ktiles, nsplit;
     float scale, scale_log2;
 };
@@ -84,7 +85,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x, split = SPLIT ? blockIdx.x % nsplit : 0;
     const int g = blockIdx.y, b = blockIdx.z;
     const int S = p.S;
-    const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
     const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
     const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
 
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         const int key_c = key < S ? key : S - 1;
 #pragma unroll
         for (int kk = 0; kk < NS; ++kk) {
-            kreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + (size_t)key_c * kv_row_stride + 16 * kk + 8 * hi));
+            kreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + p.kvmap.off(key_c) + 16 * kk + 8 * hi));
         }
     }
     int wave_hi_min = S, wg_hi_max = S;
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     constexpr int PW = Dma::PER_WAVE;
     constexpr int GROUP = 1 + 2 * PW;
     static_assert(GROUP <= NS, "one load per slot of the S phase");
-    const uint32_t stride_b = (uint32_t)(q_row_stride * 2);
+    const uint32_t stride_b = p.qmap.row_stride * 2;
     // byte offset, from the tile's first row, of the 16 bytes this lane fetches in its K-th load; rows past
     // `lim` (tile-relative) re-read row `lim` (they are never used unmasked)
     auto lane_off = [&](int K, int lim) __attribute__((always_inline)) {
@@ -170,25 +170,28 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     // the step being loaded: scalar byte pointers to its tile in q, dO and the per-row scalars
     struct LoadCursor { const char* q; const char* dO; const char* aux; int it, left; };
     LoadCursor dc;
+    // byte offsets of the current head (inside the batch entry) in q/dO and of the current tile's rows
+    size_t q_head_b = ((size_t)b * S * p.Hq + (size_t)g * p.G + head_first) * D * 2;
     {
-        const size_t head0 = ((size_t)b * S * p.Hq + (size_t)g * p.G + head_first) * D * 2;
         dc.it = it_first;
-        dc.q = reinterpret_cast<const char*>(p.q) + head0 + (size_t)dc.it * BMQ * stride_b;
-        dc.dO = reinterpret_cast<const char*>(p.dO) + head0 + (size_t)dc.it * BMQ * stride_b;
+        const size_t off = p.qmap.off(dc.it * BMQ) * 2;
+        dc.q = reinterpret_cast<const char*>(p.q) + q_head_b + off;
+        dc.dO = reinterpret_cast<const char*>(p.dO) + q_head_b + off;
         dc.aux = reinterpret_cast<const char*>(p.aux) + (((size_t)b * p.Hq + (size_t)g * p.G + head_first) * (p.S_pad / 32) + dc.it) * 256;
         dc.left = total - 1;
     }
-    const size_t tile_step_b = (size_t)BMQ * stride_b;
-    const size_t head_jump_b = (size_t)D * 2 + (size_t)(n_it - 1) * tile_step_b;          // first tile of a head -> last tile of the next
     const size_t aux_jump_b = ((size_t)(p.S_pad / 32) + (size_t)(n_it - 1)) * 256;
     auto advance_load = [&]() __attribute__((always_inline)) {
         if (dc.left > 0) {  // past the last step the cursor stays (the padding steps re-read the last tile)
             --dc.left;
-            if (dc.it == it_begin) {
-                dc.it = it_end - 1; dc.q += head_jump_b; dc.dO += head_jump_b; dc.aux += aux_jump_b;
+            if (dc.it == it_begin) {  // first tile of a head -> last tile of the next
+                dc.it = it_end - 1; q_head_b += (size_t)D * 2; dc.aux += aux_jump_b;
             } else {
-                dc.it -= 1; dc.q -= tile_step_b; dc.dO -= tile_step_b; dc.aux -= 256;
+                dc.it -= 1; dc.aux -= 256;
             }
+            const size_t off = q_head_b + p.qmap.off(dc.it * BMQ) * 2;
+            dc.q = reinterpret_cast<const char*>(p.q) + off;
+            dc.dO = reinterpret_cast<const char*>(p.dO) + off;
         }
     };
     auto issue_load = [&](auto KC, int buf) __attribute__((always_inline)) {
@@ -214,8 +217,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int it_mask_hi = (wave_hi_min - 31 + BMQ - 1) / BMQ;
     {
         TileDma<D, BNK, kWaves> vdma;
-        vdma.init(wave, lane, kv_row_stride);
-        vdma.issue(vb, j0, S - 1, reinterpret_cast<__bf16*>(smem + VS), wave);
+        vdma.init(wave, lane, p.kvmap.row_stride);
+        vdma.issue(vb + p.kvmap.off(j0), S - 1 - j0, reinterpret_cast<__bf16*>(smem + VS), wave);
         static_for<1, PW + 1>([&](auto K) { issue_load(K, 3); });  // Q rows of step 0 again, as the stand-in
         static_for<0, GROUP>([&](auto K) { issue_load(K, 0); });
         advance_load();
@@ -505,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 for (int r = 0; r < 16; ++r) {
                     const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
                     if (krow < S) {
-                        const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
+                        const size_t off = ((size_t)b * S * p.Hkv + g) * D + p.kvmap.off(krow) + 32 * db + lo;
                         p.dk[off] = (__bf16)(dkacc[kbk][db][r] * p.scale);
                         p.dv[off] = (__bf16)dvacc[kbk][db][r];
                     }
@@ -513,12 +516,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     }
 }
 
-// dK = scale * sum of the chunks' partial sums, dV = sum of theirs; four elements per thread
+// dK = scale * sum of the chunks' partial sums, dV = sum of theirs; four elements per thread.  The
+// partial sums are dense [B, S, Hkv*D]; the outputs follow `map`.
 __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restrict__ part, __bf16* __restrict__ dk,
                                                          __bf16* __restrict__ dv, int64_t n_out, int32_t nsplit,
-                                                         float scale) {
+                                                         float scale, RowMap map, int32_t S, int32_t HD) {
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= n_out) return;  // n_out is a multiple of 4 (D is)
+    const int64_t br = i / HD;  // b*S + row
+    const int64_t bb = br / S;
+    const size_t o = (size_t)bb * S * HD + map.off((int32_t)(br - bb * S)) + (size_t)(i - br * HD);
     f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
     for (int32_t s = 0; s < nsplit; ++s) {
         sk += *reinterpret_cast<const f32x4*>(part + (size_t)s * n_out + i);
@@ -527,8 +534,8 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restric
     u32x2 wk, wv;
     wk[0] = pack_bf16(sk[0] * scale, sk[1] * scale); wk[1] = pack_bf16(sk[2] * scale, sk[3] * scale);
     wv[0] = pack_bf16(sv[0], sv[1]); wv[1] = pack_bf16(sv[2], sv[3]);
-    *reinterpret_cast<u32x2*>(dk + i) = wk;
-    *reinterpret_cast<u32x2*>(dv + i) = wv;
+    *reinterpret_cast<u32x2*>(dk + o) = wk;
+    *reinterpret_cast<u32x2*>(dv + o) = wv;
 }
 
 template <int D, bool VARLEN>
@@ -537,6 +544,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
     p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
     p.S = a.S; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_ktiles = (a.S + BNK - 1) / BNK;
     p.nsplit = a.dkdv_splits; p.part = a.dkdv_part;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
@@ -549,7 +557,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
         const int64_t n_out = (int64_t)a.B * a.S * a.Hkv * D;
         const int64_t blocks = (n_out / 4 + 255) / 256;
         hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p.part, p.dk, p.dv, n_out,
-                           p.nsplit, p.scale);
+                           p.nsplit, p.scale, a.kvmap, a.S, a.Hkv * D);
     }
     return launch_status();
 }

@@ -48,6 +48,7 @@ struct DqParams {
     const float* lse; const float* delta;
     __bf16* dq;
     const int32_t* row_lo;
+    RowMap qmap, kvmap;
     int32_t S, Hq, Hkv, G, n_qtiles;
     float scale, scale_log2;
 };
@@ -69,7 +70,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
     const int b = blockIdx.y, g = h / p.G;
     const int S = p.S;
-    const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
     const __bf16* qb_ = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + h) * D;
 
@@ -85,8 +85,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
         const int rc = row < S ? row : S - 1;
 #pragma unroll
         for (int kk = 0; kk < NS; ++kk) {
-            qreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qb_ + (size_t)rc * q_row_stride + 16 * kk + 8 * hi));
-            doreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(dob + (size_t)rc * q_row_stride + 16 * kk + 8 * hi));
+            qreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qb_ + p.qmap.off(rc) + 16 * kk + 8 * hi));
+            doreg[qb][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(dob + p.qmap.off(rc) + 16 * kk + 8 * hi));
         }
         const float ls = -p.lse[((size_t)b * p.Hq + h) * S + rc] / p.scale;
         const float dl = -p.delta[((size_t)b * p.Hq + h) * S + rc];
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     constexpr int PW = Dma::PER_WAVE;
     constexpr int GROUP = 2 * PW;
     static_assert(GROUP <= NS, "one load per slot of the S phase");
-    const uint32_t stride_b = (uint32_t)(kv_row_stride * 2);
+    const uint32_t stride_b = p.kvmap.row_stride * 2;
     // byte offset, from the tile's first row, of the 16 bytes this lane fetches in its K-th load; rows past
     // `lim` (tile-relative) re-read row `lim` (they are never used unmasked)
     auto lane_off = [&](int K, int lim) __attribute__((always_inline)) {
@@ -148,17 +148,21 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     // the step being loaded: scalar byte pointers to its tile in k and v
     struct LoadCursor { const char* k; const char* v; int jt, left; };
     LoadCursor dc;
+    const size_t head0 = ((size_t)b * S * p.Hkv + g) * D * 2;
+    const char* const k_head = reinterpret_cast<const char*>(p.k) + head0;
+    const char* const v_head = reinterpret_cast<const char*>(p.v) + head0;
     {
-        const size_t head0 = ((size_t)b * S * p.Hkv + g) * D * 2;
         dc.jt = jt_begin;
-        dc.k = reinterpret_cast<const char*>(p.k) + head0 + (size_t)dc.jt * BN * stride_b;
-        dc.v = reinterpret_cast<const char*>(p.v) + head0 + (size_t)dc.jt * BN * stride_b;
+        const size_t off = p.kvmap.off(dc.jt * BN) * 2;
+        dc.k = k_head + off;
+        dc.v = v_head + off;
         dc.left = total - 1;
     }
-    const size_t tile_step_b = (size_t)BN * stride_b;
     auto advance_load = [&]() __attribute__((always_inline)) {
         if (dc.left > 0) {  // past the last step the cursor stays (the padding steps re-read the last tile)
-            --dc.left; dc.jt += 1; dc.k += tile_step_b; dc.v += tile_step_b;
+            --dc.left; dc.jt += 1;
+            const size_t off = p.kvmap.off(dc.jt * BN) * 2;
+            dc.k = k_head + off; dc.v = v_head + off;
         }
     };
     auto issue_load = [&](auto KC, int buf) __attribute__((always_inline)) {
@@ -378,7 +382,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     for (int qb = 0; qb < 2; ++qb) {
         const int row = wrow0 + 32 * qb + lo;
         if (row < S) {
-            __bf16* out = p.dq + (((size_t)b * S + row) * p.Hq + h) * D;
+            __bf16* out = p.dq + ((size_t)b * S * p.Hq + h) * D + p.qmap.off(row);
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -398,6 +402,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
     p.lse = a.lse; p.delta = a.delta; p.dq = (__bf16*)a.dq; p.row_lo = a.row_lo;
     p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
     dim3 grid(p.n_qtiles * a.Hq, a.B);

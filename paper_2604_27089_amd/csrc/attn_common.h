@@ -302,20 +302,16 @@ struct TileDma {
             chunk_b[k] = (uint32_t)(((lane % CH) ^ swz<D>(row[k])) * 16);
         }
     }
-    // The K-th of this wave's PER_WAVE loads for the tile whose first row is first_row; rows
-    // past last_valid_row re-read last_valid_row (their values are never used unmasked).
-    // Branch-free, so it can sit inside software-pipelined code.
+    // The K-th of this wave's PER_WAVE loads for the tile whose first row is at `tile` (a scalar
+    // address); rows past the tile-relative row `lim` re-read row `lim` (their values are never used
+    // unmasked).  Branch-free, so it can sit inside software-pipelined code.
     template <int K>
-    __device__ __forceinline__ void issue_one(const __bf16* gbase, int first_row, int last_valid_row,
-                                              __bf16* lds, int wave) const {
-        const char* tile = reinterpret_cast<const char*>(gbase) + (size_t)first_row * stride_b;  // scalar
-        const int lim = last_valid_row - first_row;
+    __device__ __forceinline__ void issue_one(const __bf16* tile, int lim, __bf16* lds, int wave) const {
         const int r = row[K] < lim ? row[K] : lim;
-        dma16(tile + ((uint32_t)r * stride_b + chunk_b[K]), lds + (wave + NW * K) * 512);
+        dma16(reinterpret_cast<const char*>(tile) + ((uint32_t)r * stride_b + chunk_b[K]), lds + (wave + NW * K) * 512);
     }
-    __device__ __forceinline__ void issue(const __bf16* gbase, int first_row, int last_valid_row,
-                                          __bf16* lds, int wave) const {
-        static_for<0, PER_WAVE>([&](auto K) { issue_one<decltype(K)::value>(gbase, first_row, last_valid_row, lds, wave); });
+    __device__ __forceinline__ void issue(const __bf16* tile, int lim, __bf16* lds, int wave) const {
+        static_for<0, PER_WAVE>([&](auto K) { issue_one<decltype(K)::value>(tile, lim, lds, wave); });
     }
 };
 

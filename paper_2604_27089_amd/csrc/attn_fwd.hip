@@ -36,6 +36,7 @@ struct FwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v;
     __bf16* o; float* lse;
     const int32_t* row_lo;
+    RowMap qmap, kvmap;
     int32_t S, Hq, Hkv, G, n_qtiles;
     float scale_log2;  // softmax_scale * log2(e)
 };
@@ -61,7 +62,6 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
     const int b = blockIdx.y, g = h / p.G;
     const int S = p.S;
-    const size_t q_row_stride = (size_t)p.Hq * D, kv_row_stride = (size_t)p.Hkv * D;
     const __bf16* qb = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
     const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     bf16x8 qreg[D / 16];
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk)
-        qreg[kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qb + (size_t)qrow_c * q_row_stride + 16 * kk + 8 * hi));
+        qreg[kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qb + p.qmap.off(qrow_c) + 16 * kk + 8 * hi));
 
     int row_lo = 0, wave_lo_min = 0, wave_lo_max = 0, wg_lo_min = 0;
     if (VARLEN) {
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
             voff[half][db] = tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
 
     TileDma<D, BN, kWaves> dma;
-    dma.init(wave, lane, kv_row_stride);
+    dma.init(wave, lane, p.kvmap.row_stride);
 
     f32x16 oacc[D / 32];
 #pragma unroll
@@ -256,8 +256,8 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
 
     // pair j = (K tile j, V tile j-1) -> the given buffers
     auto issue_pair = [&](__bf16* kbuf, __bf16* vbuf, int j) __attribute__((always_inline)) {
-        if (j < T) dma.issue(kb, (jt_begin + j) * BN, S - 1, kbuf, wave);
-        if (j >= 1 && j <= T) dma.issue(vb, (jt_begin + j - 1) * BN, S - 1, vbuf, wave);
+        if (j < T) dma.issue(kb + p.kvmap.off((jt_begin + j) * BN), S - 1 - (jt_begin + j) * BN, kbuf, wave);
+        if (j >= 1 && j <= T) dma.issue(vb + p.kvmap.off((jt_begin + j - 1) * BN), S - 1 - (jt_begin + j - 1) * BN, vbuf, wave);
     };
 
     issue_pair(ks0, vs0, 0);
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     const float l_tot = l_run + xhalf(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (qrow < S) {
-        __bf16* orow = p.o + (((size_t)b * S + qrow) * p.Hq + h) * D;
+        __bf16* orow = p.o + ((size_t)b * S * p.Hq + h) * D + p.qmap.off(qrow);
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -317,6 +317,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v;
     p.o = (__bf16*)a.o; p.lse = a.lse; p.row_lo = a.row_lo;
     p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale_log2 = a.scale * kLog2e;
     dim3 grid(p.n_qtiles * a.Hq, a.B), block(kThreads);

@@ -31,6 +31,20 @@ sp_status check_attn_shape(int64_t B, int64_t S, int32_t Hq, int32_t Hkv, int32_
 
 inline float resolve_scale(float s, int32_t D) { return s > 0.f ? s : 1.0f / sqrtf((float)D); }
 
+inline void attention_side_maps(sp::AttnArgs& a) {
+    a.qmap = sp::RowMap::attention_side(a.Hq, a.D);
+    a.kvmap = sp::RowMap::attention_side(a.Hkv, a.D);
+}
+
+// sequence-side calls: S_l must be a power of two and a multiple of the largest tile (256 rows), so that
+// no tile of any kernel straddles two peers' chunks; returns log2(S_l) or -1
+inline int32_t seq_chunk_log2(int64_t S_l) {
+    if (S_l < 256 || (S_l & (S_l - 1)) != 0 || S_l >= ((int64_t)1 << 31)) return -1;
+    int32_t l = 0;
+    while (((int64_t)1 << l) < S_l) ++l;
+    return l;
+}
+
 // Workspace layout: [delta fp32 B*Hq*S] [per-row seeds fp32 2*B*Hq*S_pad: per 32-row tile, 32 x -LSE/scale
 // then 32 x -Delta] (bwd only)
 // [row_lo int32 T] [row_hi int32 T] (varlen only)
@@ -108,6 +122,29 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    attention_side_maps(a);
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_fwd_seqlayout(const void* q, const void* k, const void* v, void* o, float* lse,
+                                int64_t B, int64_t S_l, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                                float softmax_scale, void* hip_stream) {
+    if (P <= 0 || S_l < 0) return SP_ERR_SHAPE;
+    sp_status st = check_attn_shape(B, S_l * P, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (B == 0 || S_l == 0 || Hq == 0) return SP_OK;
+    const int32_t lg = seq_chunk_log2(S_l);
+    if (lg < 0) return SP_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
+    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
+        !sp::aligned16(lse))
+        return SP_ERR_ALIGN;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.B = (int32_t)B; a.S = (int32_t)(S_l * P); a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
+    a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
     a.scale = resolve_scale(softmax_scale, D);
     return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
 }
@@ -140,8 +177,41 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
     a.S_pad = sp::aux_pitch(S);
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = stages;
+    a.dkdv_splits = sp::dkdv_split_count(B, S, Hq, Hkv);
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
+    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, const void* o,
+                                const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, int64_t B, int64_t S_l,
+                                int32_t Hq, int32_t Hkv, int32_t D, int32_t P, float softmax_scale,
+                                void* hip_stream) {
+    if (P <= 0 || S_l < 0) return SP_ERR_SHAPE;
+    const int64_t S = S_l * P;
+    sp_status st = check_attn_shape(B, S, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (B == 0 || S == 0 || Hq == 0) return SP_OK;
+    const int32_t lg = seq_chunk_log2(S_l);
+    if (lg < 0) return SP_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0)) return SP_ERR_WORKSPACE;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
+    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
+    a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
+    a.S_pad = sp::aux_pitch(S);
+    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
+    a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
+    a.scale = resolve_scale(softmax_scale, D);
+    a.stages = SP_BWD_STAGE_ALL;
     a.dkdv_splits = sp::dkdv_split_count(B, S, Hq, Hkv);
     a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
     return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
@@ -171,6 +241,7 @@ sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* 
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse; a.row_lo = row_lo; a.row_hi = row_hi;
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     return sp::launch_attn_fwd(a, s);
 }
@@ -205,6 +276,7 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
     a.aux = aux; a.S_pad = sp::aux_pitch(T);
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
     a.dkdv_splits = sp::dkdv_split_count(1, T, Hq, Hkv);

@@ -14,6 +14,28 @@ inline sp_status launch_status() {
     return hipGetLastError() == hipSuccess ? SP_OK : SP_ERR_LAUNCH;
 }
 
+// Where row r (0 <= r < S) of an attention-side [S, H, D] tensor lives, in elements from the start of
+// its batch entry (the head offset h*D comes on top).  Two layouts are served by the same kernels:
+//   attention-side  [S, H, D]        : r * H*D
+//   sequence-side   [S_l, P*H, D]    : (r % S_l) * P*H*D + (r / S_l) * H*D
+// the second being the tensor whose pack (seq -> head re-layout) is the first: reading through this map
+// folds the pack into the attention kernels' loads and the unpack into their stores.  S_l is a power
+// of two there (mask/shift); the attention-side case uses shift 31, so r >> shift is 0 for every row.
+// A batch entry spans S*H*D elements in both layouts.
+struct RowMap {
+    uint32_t mask;          // S_l - 1, or 0x7fffffff
+    int32_t shift;          // log2(S_l), or 31
+    uint32_t row_stride;    // elements between consecutive rows of a chunk
+    uint32_t chunk_stride;  // elements between chunk p and chunk p+1 (H*D, or 0)
+    __host__ __device__ size_t off(int32_t r) const {
+        return (size_t)((uint32_t)r & mask) * row_stride + (size_t)((uint32_t)r >> shift) * chunk_stride;
+    }
+    static RowMap attention_side(int32_t H, int32_t D) { return RowMap{0x7fffffffu, 31, (uint32_t)(H * D), 0u}; }
+    static RowMap sequence_side(int32_t S_l_log2, int32_t H, int32_t D, int32_t P) {
+        return RowMap{(1u << S_l_log2) - 1u, S_l_log2, (uint32_t)(P * H * D), (uint32_t)(H * D)};
+    }
+};
+
 // One attention problem as the kernels see it.  Dense calls are B independent
 // sequences of S rows; packed-document calls are B = 1, S = T rows with a
 // per-row visibility window taken from `row_lo` / `row_hi`.
@@ -28,6 +50,7 @@ struct AttnArgs {
     const int32_t* row_lo;  // varlen: first row of the row's document, [S]; null if dense
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
     int32_t B, S, Hq, Hkv, D;
+    RowMap qmap, kvmap;     // layout of q, o, dO, dq and of k, v, dk, dv
     float scale;            // softmax scale (already defaulted)
     int32_t stages;         // bwd: bit mask of SP_BWD_STAGE_*
     int32_t dkdv_splits;    // bwd: workgroups that share one key tile of the dK/dV kernel (dkdv_split_count)

@@ -78,6 +78,18 @@ def test_attention_argument_errors():
     assert vf(A(1), A(2), A(3), A(4), A(5), A(6), 2, 0, 1024, 4, 1, 128, 0.0, A(7), 16, None) == sp.SP_ERR_WORKSPACE
     vb = L.sp_attn_varlen_bwd
     assert vb(*args[:9], A(11), 2, 0, 1024, 4, 1, 128, 0.0, A(12), 16, None) == sp.SP_ERR_WORKSPACE
+    # sequence-side calls: S_l must be a power of two >= 256
+    sf = L.sp_attn_fwd_seqlayout
+    assert sf(A(1), A(2), A(3), A(4), A(5), 1, 384, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_UNSUPPORTED
+    assert sf(A(1), A(2), A(3), A(4), A(5), 1, 128, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_UNSUPPORTED
+    assert sf(A(1), A(2), A(3), A(4), A(5), 1, 512, 4, 1, 128, 0, 0.0, None) == sp.SP_ERR_SHAPE
+    assert sf(A(1), A(2), A(3), A(4), A(5), 1, 512, 4, 3, 128, 8, 0.0, None) == sp.SP_ERR_SHAPE
+    assert sf(None, A(2), A(3), A(4), A(5), 1, 512, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_NULL
+    assert sf(None, None, None, None, None, 1, 0, 4, 1, 128, 8, 0.0, None) == sp.SP_OK
+    sb = L.sp_attn_bwd_seqlayout
+    need8 = sp.sp_attn_bwd_workspace_bytes(1, 8 * 512, 4, 1, 128, 0)
+    assert sb(*args, need8 - 1, 1, 512, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_WORKSPACE
+    assert sb(*args, need8, 1, 500, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_UNSUPPORTED
 
 
 def test_binding_fails_loudly_without_library(monkeypatch):
