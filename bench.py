@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip recompute/varlen/pack extras")
+    ap.add_argument("--no-other-shards", action="store_true",
+                    help="skip the other models' shards and the folded step (keeps per-kernel profiles of one shape)")
     return ap.parse_args()
 
 
@@ -214,6 +216,34 @@ def main():
         tb = time_fn(lambda: sp.sp_attn_varlen_bwd(vq, vk, vv, vo, vlse, vdo, cu, dq=vdq, dk=vdk, dv=vdv, workspace=vws), 10)
         detail["varlen"] = {"T": T, "n_docs": len(lengths), "max_len": max(lengths), "fwd_ms": tf, "bwd_ms": tb,
                             "fwd_bwd_tflops": 14.0 * D * vc["Hq"] * vp / ((tf + tb) * 1e-3) / 1e12}
+
+        # the head shards (at P=8) of the other models the paper evaluates (Section 4 setup: Llama-3.2 1B and
+        # 3B, Llama-2 13B; head counts from their public configurations), 64K rows, and the 70B-shaped shard
+        shapes = [("llama3.2-1b: 4q/1kv D=64", 65536, 4, 1, 64), ("llama3.2-3b: 3q/1kv D=128", 65536, 3, 1, 128),
+                  ("llama2-13b: 5q/5kv (full attention) D=128", 65536, 5, 5, 128),
+                  ("70b-shaped: 8q/1kv D=128", 131072, 8, 1, 128), ("c2_8b_32k: 4q/1kv D=128", 32768, 4, 1, 128)]
+        detail["other_shards"] = []
+        for name, Sx, hq, hkv, d in ([] if args.no_other_shards else shapes):
+            xq, xdo = (torch.empty((1, Sx, hq, d), **bf).normal_() for _ in range(2))
+            xk, xv = (torch.empty((1, Sx, hkv, d), **bf).normal_() for _ in range(2))
+            xo, xlse = sp.sp_attn_fwd(xq, xk, xv)
+            xws = torch.empty(sp.sp_attn_bwd_workspace_bytes(1, Sx, hq, hkv, d, 0), dtype=torch.uint8, device=dev)
+            xdq, xdk, xdv = torch.empty_like(xq), torch.empty_like(xk), torch.empty_like(xv)
+            n = 3 if Sx > 65536 else 5
+            tf = time_fn(lambda: sp.sp_attn_fwd(xq, xk, xv, o=xo, lse=xlse), n, 1)
+            tb = time_fn(lambda: sp.sp_attn_bwd(xq, xk, xv, xo, xlse, xdo, dq=xdq, dk=xdk, dv=xdv, workspace=xws), n, 1)
+            fl = 14.0 * d * hq * (Sx * (Sx + 1) // 2)
+            detail["other_shards"].append({"shard": name, "S": Sx, "fwd_ms": tf, "bwd_ms": tb,
+                                           "fwd_bwd_tflops": fl / ((tf + tb) * 1e-3) / 1e12})
+            del xq, xdo, xk, xv, xo, xlse, xws, xdq, xdk, xdv
+        # the same step with the re-layouts folded into the attention kernels (sequence-side tensors in and out)
+        o_s, dq_s, dk_s, dv_s = torch.empty_like(q_l), torch.empty_like(q_l), torch.empty_like(k_l), torch.empty_like(k_l)
+        def folded():
+            sp.sp_attn_fwd_seqlayout(q_l, k_l, v_l, P, o=o_s, lse=lse)
+            sp.sp_attn_bwd_seqlayout(q_l, k_l, v_l, o_s, lse, do_l, P, dq=dq_s, dk=dk_s, dv=dv_s, workspace=ws)
+        if not args.no_other_shards:
+            t = time_fn(folded, max(3, args.steps // 2), 1)
+            detail["seqlayout_step"] = {"ms": t, "fwd_bwd_tflops": (fl_fwd + fl_bwd) / (t * 1e-3) / 1e12}
 
     out = {
         "metric": "causal attn fwd+bwd TFLOP/s at S=128K,D=128 (% bf16 MFMA peak); pack GB/s",

@@ -21,6 +21,8 @@ SMALL = [
     (257, 8, 2, 64, 1),
     (1000, 4, 1, 128, 1),  # several tiles, ragged tail
     (700, 2, 2, 128, 2),
+    (600, 3, 1, 128, 1),   # Llama-3.2 3B-shaped shard: 3 query heads on one KV head
+    (520, 5, 5, 128, 1),   # Llama-2 13B-shaped shard: full attention, 5 heads
     (2100, 1, 1, 128, 1),  # one head: each key tile's row steps shared by two workgroups
     (3000, 4, 1, 64, 1),   # eight workgroups per key tile, chunks crossing head boundaries
 ]

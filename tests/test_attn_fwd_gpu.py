@@ -21,6 +21,8 @@ SMALL = [
     (200, 8, 2, 128, 1),
     (1000, 4, 1, 128, 1),  # several tiles and a ragged tail
     (777, 2, 2, 64, 3),
+    (600, 3, 1, 128, 1),   # Llama-3.2 3B-shaped shard: 3 query heads on one KV head
+    (520, 5, 5, 128, 1),   # Llama-2 13B-shaped shard: full attention, 5 heads
 ]
 
 
