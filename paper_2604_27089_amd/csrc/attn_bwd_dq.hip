@@ -140,10 +140,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
         const uint32_t chunk_b = (uint32_t)(((lane % Dma::CH) ^ swz<D>(row)) * 16);
         return (uint32_t)(row < lim ? row : lim) * stride_b + chunk_b;
     };
-    uint32_t voff[PW];
+    uint32_t voff[PW];  // offsets of the tile the load cursor is on
 #pragma unroll
     for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, BN - 1);
     const int jt_tail = (S % BN != 0) ? (S - 1) / BN : -1;  // the tile that runs past the last row, if any
+    const int tiles_per_chunk_mask = (int)(p.kvmap.mask / BN);  // tiles per peer chunk - 1 (chunks are powers of two)
 
     // the step being loaded: scalar byte pointers to its tile in k and v
     struct LoadCursor { const char* k; const char* v; int jt, left; };
@@ -151,27 +152,39 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const size_t head0 = ((size_t)b * S * p.Hkv + g) * D * 2;
     const char* const k_head = reinterpret_cast<const char*>(p.k) + head0;
     const char* const v_head = reinterpret_cast<const char*>(p.v) + head0;
+    const size_t tile_step_b = (size_t)BN * stride_b;
+    // The tail tile is the last one the cursor can reach, and the cursor stays on it: its clamped lane offsets
+    // replace the regular ones for good.
+    auto enter_tile = [&]() __attribute__((always_inline)) {
+        if (dc.jt == jt_tail) {  // rare
+#pragma unroll
+            for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, S - 1 - dc.jt * BN);
+        }
+    };
     {
         dc.jt = jt_begin;
         const size_t off = p.kvmap.off(dc.jt * BN) * 2;
         dc.k = k_head + off;
         dc.v = v_head + off;
         dc.left = total - 1;
+        enter_tile();
     }
     auto advance_load = [&]() __attribute__((always_inline)) {
         if (dc.left > 0) {  // past the last step the cursor stays (the padding steps re-read the last tile)
             --dc.left; dc.jt += 1;
-            const size_t off = p.kvmap.off(dc.jt * BN) * 2;
-            dc.k = k_head + off; dc.v = v_head + off;
+            dc.k += tile_step_b; dc.v += tile_step_b;
+            if ((dc.jt & tiles_per_chunk_mask) == 0) {  // rare: the first tile of the next peer's chunk
+                const size_t off = p.kvmap.off(dc.jt * BN) * 2;
+                dc.k = k_head + off; dc.v = v_head + off;
+            }
+            enter_tile();
         }
     };
     auto issue_load = [&](auto KC, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(KC)::value, KK = K % PW;
-        uint32_t off = voff[KK];
-        if (dc.jt == jt_tail) off = lane_off(KK, S - 1 - dc.jt * BN);  // rare
         const char* src = K < PW ? dc.k : dc.v;
         char* dst = smem + (K < PW ? KS : VS) + buf * TILE_B + (wave + kWaves * KK) * 1024;
-        dma16(src + off, dst);
+        dma16(src + voff[KK], dst);
     };
 
     // ---- prologue: the first LEAD steps' tiles, and a finite stand-in for the deferred dQ of "step -1" ----
@@ -290,6 +303,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
                 __builtin_amdgcn_sched_barrier(0);
                 issue_slot();
                 if constexpr (s < GROUP) issue_load(SC, DBUF);
+                // the cursor moves on in the first slot without a load (scalar work between the slot's read and
+                // its second MFMA, where the compiler would otherwise put a wait state)
+                if constexpr (s == GROUP) advance_load();
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (s == 0) mfma_vc_ab<-1>(sacc[1], ak[s], qreg[1][s], seed_s[1]);
                 else mfma_v_ab<-1>(sacc[1], ak[s], qreg[1][s]);
@@ -347,7 +363,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
         __builtin_amdgcn_sched_barrier(0);
         ++step_no;
         if (step_no < total) cur_jt += 1;
-        advance_load();
+        if constexpr (GROUP >= NS) advance_load();
     };
 
     // Eight steps per iteration, one per ring position; the step count is rounded up to a multiple of
