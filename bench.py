@@ -84,6 +84,71 @@ def cpu_baseline(seed: int, Hq: int, Hkv: int, D: int, target_s: float = 15.0):
                       f"{Hq}q/{Hkv}kv D={D} workload, {t:.1f} s"}
 
 
+def sample_clocks(run_once, seconds: float = 2.0):
+    """Run `run_once` in a loop for about `seconds` while a thread samples the shader clock (amdsmi, else
+    rocm-smi).  Returns {"sclk_mhz": [min, mean, max], "power_w": mean or None, "samples": n} or None."""
+    import threading
+    import torch
+    reader = None
+    try:
+        import amdsmi
+        amdsmi.amdsmi_init()
+        h = amdsmi.amdsmi_get_processor_handles()[0]
+
+        def reader():
+            c = amdsmi.amdsmi_get_clock_info(h, amdsmi.AmdSmiClkType.GFX)
+            clk = float(c.get("clk", c.get("cur_clk", 0)))
+            try:
+                pw = amdsmi.amdsmi_get_power_info(h)
+                w = float(pw.get("current_socket_power", pw.get("average_socket_power", 0)) or 0)
+            except Exception:
+                w = 0.0
+            return clk, w
+        reader()
+    except Exception:
+        import re
+        import subprocess
+
+        def reader():
+            o = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=5).stdout
+            m = re.search(r'"sclk clock speed:": "\((\d+)Mhz\)"', o)
+            return (float(m.group(1)) if m else 0.0), 0.0
+        try:
+            reader()
+        except Exception:
+            return None
+    clks, pws, stop = [], [], threading.Event()
+
+    def loop():
+        while not stop.is_set():
+            try:
+                c, w = reader()
+                if c > 0:
+                    clks.append(c)
+                if w > 0:
+                    pws.append(w)
+            except Exception:
+                pass
+            time.sleep(0.02)
+
+    t = threading.Thread(target=loop, daemon=True)
+    run_once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    t.start()
+    while time.perf_counter() - t0 < seconds:
+        run_once()
+        run_once()
+        torch.cuda.synchronize()
+    stop.set()
+    t.join(timeout=5)
+    clks = [c for c in clks if c >= 500.0]  # a sample between two launches can read the idle clock
+    if not clks:
+        return None
+    return {"sclk_mhz": [min(clks), float(np.mean(clks)), max(clks)], "power_w": float(np.mean(pws)) if pws else None,
+            "samples": len(clks), "max_sclk_mhz_spec": 2400}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -244,6 +309,10 @@ def main():
         if not args.no_other_shards:
             t = time_fn(folded, max(3, args.steps // 2), 1)
             detail["seqlayout_step"] = {"ms": t, "fwd_bwd_tflops": (fl_fwd + fl_bwd) / (t * 1e-3) / 1e12}
+
+        # Shader clock (and socket power where readable) while the step runs: the published peak assumes the
+        # maximum clock, which the part does not hold under this load.
+        detail["clocks"] = sample_clocks(lambda: step(), seconds=2.0)
 
     out = {
         "metric": "causal attn fwd+bwd TFLOP/s at S=128K,D=128 (% bf16 MFMA peak); pack GB/s",
