@@ -79,9 +79,17 @@ def cpu_baseline(seed: int, Hq: int, Hkv: int, D: int, target_s: float = 15.0):
     S = int(np.sqrt(target_s * rate / (7.0 * D * Hq)))
     S = max(1024, min(16384, S // 512 * 512))
     t = run(S)
+    # the oracle's re-layout (numpy) on the 8B-shaped Q shard at 32K rows, [4096, 32, 128] bf16
+    x = synth.pack_input(seed, 1, 4096, 32, 128)[0]
+    t0 = time.perf_counter()
+    y = rn.pack_seq_to_head(x, 8)
+    rn.unpack_head_to_seq(y, 8)
+    tp = time.perf_counter() - t0
     return {"value": flops(S) / t / 1e12, "unit": "TFLOP/s", "cores": rs.num_threads(), "kind": "oracle",
             "sample": f"fp64 C oracle, forward+backward on the first {S} rows (causal prefix) of the same "
-                      f"{Hq}q/{Hkv}kv D={D} workload, {t:.1f} s"}
+                      f"{Hq}q/{Hkv}kv D={D} workload, {t:.1f} s",
+            "relayout_GBps": 4.0 * x.nbytes / tp / 1e9,
+            "relayout_sample": "numpy oracle, pack + unpack of a [4096,32,128] bf16 tensor at P=8 (one thread)"}
 
 
 def sample_clocks(run_once, seconds: float = 2.0):
@@ -231,6 +239,9 @@ def main():
     value = (fl_fwd + fl_bwd) / (ms_per_step * 1e-3) / 1e12
     detail = {
         "kernel_ms_per_step": {n: round(v, 4) for n, v in kern_ms.items()},
+        # per timed region (median, minimum over the timed steps); pack and unpack have two regions per step each
+        "kernel_ms_median": {n: round(float(np.median(v)), 4) for n, v in per.items()},
+        "kernel_ms_min": {n: round(float(np.min(v)), 4) for n, v in per.items()},
         "attn_fwd_tflops": fl_fwd / (kern_ms["attn_fwd"] * 1e-3) / 1e12,
         "attn_bwd_tflops": fl_bwd / ((kern_ms["attn_bwd_delta"] + kern_ms["attn_bwd_dkdv"] + kern_ms["attn_bwd_dq"]) * 1e-3) / 1e12,
         "pct_of_bf16_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,

@@ -76,7 +76,7 @@ def sparse_rows(S, n, seed):
     return np.unique(np.concatenate([fixed, rng.integers(0, S, n)])).astype(np.int64)
 
 
-@pytest.mark.parametrize("name,n_rows", [("c2_8b_32k", 40), ("c3_8b_128k", 24)])
+@pytest.mark.parametrize("name,n_rows", [("c2_8b_32k", 40), ("c3_8b_128k", 24), ("c4_70b_128k", 16)])
 def test_bwd_full_size_sparse_dO(name, n_rows):
     """Full-size shard in the benchmark's launch configuration.  dO is non-zero
     on a sampled set of rows only; rows with dO_i = 0 contribute nothing to any

@@ -71,7 +71,7 @@ def test_fwd_closed_forms_on_device():
     assert np.abs(host_f64(o2) - 1.25).max() <= 2 ** -7
 
 
-@pytest.mark.parametrize("name", ["c2_8b_32k", "c3_8b_128k"])
+@pytest.mark.parametrize("name", ["c2_8b_32k", "c3_8b_128k", "c4_70b_128k"])
 def test_fwd_full_size_sampled_rows(name):
     """Full-size shards in the launch configuration the benchmark times; the
     oracle computes sampled rows one by one: tile edges, the first and last
