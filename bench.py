@@ -321,6 +321,17 @@ def main():
             t = time_fn(folded, max(3, args.steps // 2), 1)
             detail["seqlayout_step"] = {"ms": t, "fwd_bwd_tflops": (fl_fwd + fl_bwd) / (t * 1e-3) / 1e12}
 
+        # What the vendor library's plain bf16 GEMM reaches on this machine at the same power cap: a practical
+        # ceiling for matrix work, like the device copy is for the re-layout.
+        ga = torch.empty((8192, 8192), **bf).normal_()
+        gb = torch.empty((8192, 8192), **bf).normal_()
+        gc = torch.empty((8192, 8192), **bf)
+        tg = time_fn(lambda: torch.matmul(ga, gb, out=gc), 50, 5)
+        detail["library_gemm_reference"] = {"what": "torch.matmul (hipBLASLt/rocBLAS) bf16 8192x8192x8192", "ms": tg,
+                                            "tflops": 2.0 * 8192 ** 3 / (tg * 1e-3) / 1e12}
+        del ga, gb, gc
+        executed = fl_fwd + 0.8 * fl_bwd + 0.6 * fl_bwd  # forward 2, dK/dV 4, dQ 3 contractions
+        detail["executed_tflops_step"] = executed / (ms_per_step * 1e-3) / 1e12
         # Shader clock (and socket power where readable) while the step runs: the published peak assumes the
         # maximum clock, which the part does not hold under this load.
         detail["clocks"] = sample_clocks(lambda: step(), seconds=2.0)
