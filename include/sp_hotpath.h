@@ -200,6 +200,44 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
                              int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------------------
+ * Pointwise operators between the matrix multiplications of a Llama layer, on
+ * one device's token shard [T = S/P tokens, full model dimension] (Section 2,
+ * Figure 1: outside attention a device holds part of the sequence with all of
+ * the model dimension).  The paper's activation-checkpointing strategy lets
+ * every operator outside the attention layer be rematerialised in the backward
+ * pass (Section 3.2), so each forward below runs twice per training step; the
+ * evaluated models are Llama models (Section 4 setup), whose published layer
+ * these operators come from.  bf16 in and out, fp32 arithmetic, one rounding.
+ *
+ * RMS norm:  y[t,c] = x[t,c] * rstd[t] * w[c],  rstd[t] = 1/sqrt(mean_c x[t,c]^2 + eps)
+ *   forward : x, y [T, C] bf16, w [C] bf16, rstd [T] fp32 (output, kept for the backward)
+ *   backward: dx = g*rstd - x*rstd^3*(sum_c g x)/C with g = dy*w;  dw = sum_t dy*x*rstd
+ *             dx [T, C], dw [C] bf16 (fp32 accumulation, fixed summation order);
+ *             workspace >= sp_rmsnorm_bwd_workspace_bytes(T, C), contents undefined.
+ *   C % 8 == 0 and C <= 8192 (SP_ERR_UNSUPPORTED otherwise).
+ *
+ * Rotary embedding:  x, out [T, H, D] bf16; cos_table, sin_table [T, D/2] fp32 hold
+ *   the cosine and sine of the angle of (token t, pair i).  Element i of the first
+ *   half of the head dim and element i of the second half form a pair:
+ *     out1 = x1*cos - x2*sin,  out2 = x2*cos + x1*sin.
+ *   conjugate != 0 rotates by the negative angle: the gradient operator.  out may
+ *   be x itself (in place); any other overlap is not allowed.  D % 16 == 0.
+ *
+ * SwiGLU gate:  y = g*sigmoid(g)*u over n = T*F elements (n % 8 == 0);
+ *   backward: dg = dy*u*s*(1 + g*(1 - s)), du = dy*g*s with s = sigmoid(g).
+ * ------------------------------------------------------------------------- */
+size_t sp_rmsnorm_bwd_workspace_bytes(int64_t T, int32_t C);
+sp_status sp_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
+                         void* hip_stream);
+sp_status sp_rmsnorm_bwd(const void* x, const void* w, const float* rstd, const void* dy, void* dx, void* dw,
+                         void* workspace, size_t workspace_bytes, int64_t T, int32_t C, void* hip_stream);
+sp_status sp_rope(const void* x, const float* cos_table, const float* sin_table, void* out, int64_t T, int32_t H,
+                  int32_t D, int32_t conjugate, void* hip_stream);
+sp_status sp_swiglu_fwd(const void* g, const void* u, void* y, int64_t n, void* hip_stream);
+sp_status sp_swiglu_bwd(const void* g, const void* u, const void* dy, void* dg, void* du, int64_t n,
+                        void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

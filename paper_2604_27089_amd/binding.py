@@ -24,6 +24,7 @@ EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
     "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
     "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
+    "sp_rmsnorm_bwd_workspace_bytes", "sp_rmsnorm_fwd", "sp_rmsnorm_bwd", "sp_rope", "sp_swiglu_fwd", "sp_swiglu_bwd",
 )
 
 
@@ -70,6 +71,18 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
     L.sp_attn_varlen_bwd.argtypes = [vp] * 10 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
+    L.sp_rmsnorm_bwd_workspace_bytes.restype = sz
+    L.sp_rmsnorm_bwd_workspace_bytes.argtypes = [i64, i32]
+    L.sp_rmsnorm_fwd.restype = c.c_int
+    L.sp_rmsnorm_fwd.argtypes = [vp, vp, vp, vp, i64, i32, f32, vp]
+    L.sp_rmsnorm_bwd.restype = c.c_int
+    L.sp_rmsnorm_bwd.argtypes = [vp] * 7 + [sz, i64, i32, vp]
+    L.sp_rope.restype = c.c_int
+    L.sp_rope.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    L.sp_swiglu_fwd.restype = c.c_int
+    L.sp_swiglu_fwd.argtypes = [vp, vp, vp, i64, vp]
+    L.sp_swiglu_bwd.restype = c.c_int
+    L.sp_swiglu_bwd.argtypes = [vp] * 5 + [i64, vp]
     _lib = L
     return L
 
@@ -233,6 +246,54 @@ def sp_attn_varlen_bwd(q, k, v, o, lse, do, cu_seqlens, max_seqlen: int = 0, sof
                                     Hkv, D, float(softmax_scale), _ptr(workspace), workspace.numel(),
                                     _stream(stream)), "sp_attn_varlen_bwd")
     return dq, dk, dv
+
+
+# --------------------------------------------------------------------------- pointwise operators
+def sp_rmsnorm_fwd(x, w, eps: float, y=None, rstd=None, stream=None):
+    """x [T, C] bf16, w [C] bf16 -> (y [T, C] bf16, rstd [T] fp32)."""
+    T, C = x.shape
+    y = torch.empty_like(x) if y is None else y
+    rstd = torch.empty((T,), dtype=torch.float32, device=x.device) if rstd is None else rstd
+    _check(lib().sp_rmsnorm_fwd(_ptr(x), _ptr(w), _ptr(y), _ptr(rstd), T, C, float(eps), _stream(stream)), "sp_rmsnorm_fwd")
+    return y, rstd
+
+
+def sp_rmsnorm_bwd_workspace_bytes(T, C) -> int:
+    return int(lib().sp_rmsnorm_bwd_workspace_bytes(T, C))
+
+
+def sp_rmsnorm_bwd(x, w, rstd, dy, dx=None, dw=None, workspace=None, stream=None):
+    """Returns (dx [T, C], dw [C]) bf16."""
+    T, C = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dw = torch.empty_like(w) if dw is None else dw
+    if workspace is None:
+        workspace = _workspace(sp_rmsnorm_bwd_workspace_bytes(T, C), x.device)
+    _check(lib().sp_rmsnorm_bwd(_ptr(x), _ptr(w), _ptr(rstd), _ptr(dy), _ptr(dx), _ptr(dw), _ptr(workspace),
+                                workspace.numel(), T, C, _stream(stream)), "sp_rmsnorm_bwd")
+    return dx, dw
+
+
+def sp_rope(x, cos_table, sin_table, conjugate: bool = False, out=None, stream=None):
+    """x [T, H, D] bf16, cos/sin tables [T, D/2] fp32 -> rotated tensor (out may be x)."""
+    T, H, D = x.shape
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().sp_rope(_ptr(x), _ptr(cos_table), _ptr(sin_table), _ptr(out), T, H, D, int(bool(conjugate)),
+                         _stream(stream)), "sp_rope")
+    return out
+
+
+def sp_swiglu_fwd(g, u, y=None, stream=None):
+    y = torch.empty_like(g) if y is None else y
+    _check(lib().sp_swiglu_fwd(_ptr(g), _ptr(u), _ptr(y), g.numel(), _stream(stream)), "sp_swiglu_fwd")
+    return y
+
+
+def sp_swiglu_bwd(g, u, dy, dg=None, du=None, stream=None):
+    dg = torch.empty_like(g) if dg is None else dg
+    du = torch.empty_like(u) if du is None else du
+    _check(lib().sp_swiglu_bwd(_ptr(g), _ptr(u), _ptr(dy), _ptr(dg), _ptr(du), g.numel(), _stream(stream)), "sp_swiglu_bwd")
+    return dg, du
 
 
 def default_scale(D: int) -> float:

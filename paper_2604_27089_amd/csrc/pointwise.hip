@@ -1,0 +1,307 @@
+// Pointwise operators between the matrix multiplications of a Llama layer, on
+// one device's [S/P, model dim] token shard: RMS normalisation, rotary position
+// embedding and the SwiGLU gate, forward and backward.  The paper's
+// activation-checkpointing strategy has every operator outside the attention
+// layer rematerialised in the backward pass (Section 3.2), so each of these
+// runs twice per training step; the models it evaluates are Llama models
+// (Section 4 setup).  Outside attention a device holds part of the sequence with
+// the full model dimension (Section 2, Figure 1).
+//
+// All of them stream: every element is read once and written once, in 16-byte
+// vectors with non-temporal accesses; arithmetic is fp32, results are rounded
+// to bf16 once.  HBM-bound.
+#include "sp_common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kMaxC = 8192;  // widest row the RMS-norm kernels keep in registers (16 vectors of 8 per lane)
+
+__device__ __forceinline__ void widen(const u32x4& v, float (&f)[8]) {
+    const bf16x8 b = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (float)b[e];
+}
+__device__ __forceinline__ u32x4 narrow(const float (&f)[8]) {
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const f32x2 p = {f[2 * e], f[2 * e + 1]};
+        r[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+    }
+    return r;
+}
+__device__ __forceinline__ u32x4 ld16(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+__device__ __forceinline__ void st16(void* p, const u32x4& v) { __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p)); }
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// ------------------------------------------------------------------ RMS norm, forward
+// One wave per row; the row stays in registers between the sum of squares and the scaling.
+// Lane l owns the 8-column vectors number l, l+64, ... (NV of them, C <= 512*NV).
+template <int NV>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ w,
+                                                         __bf16* __restrict__ y, float* __restrict__ rstd,
+                                                         int64_t T, int32_t C, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= T) return;
+    const __bf16* xr = x + row * C;
+    u32x4 xv[NV];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c0 = (j * 64 + lane) * 8;
+        if (c0 < C) {
+            xv[j] = ld16(xr + c0);
+            float f[8];
+            widen(xv[j], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+        }
+    }
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)C + eps);
+    if (lane == 0) rstd[row] = r;
+    __bf16* yr = y + row * C;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c0 = (j * 64 + lane) * 8;
+        if (c0 < C) {
+            float f[8], g[8];
+            widen(xv[j], f);
+            widen(*reinterpret_cast<const u32x4*>(w + c0), g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
+            st16(yr + c0, narrow(f));
+        }
+    }
+}
+
+// ------------------------------------------------------------------ RMS norm, backward
+//   g = dy * w,  dx = g * rstd - x * rstd^3 * (sum_c g x) / C,  dw = sum_t dy * x * rstd
+// One wave per row, rows dealt round-robin to the waves of a persistent grid; a lane keeps the dw terms
+// of its columns in registers over all its rows, the four waves of a workgroup add theirs through LDS
+// and the workgroup writes one fp32 partial row; rmsnorm_dw_kernel adds the partial rows in a fixed order.
+template <int NV>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ w,
+                                                         const float* __restrict__ rstd, const __bf16* __restrict__ dy,
+                                                         __bf16* __restrict__ dx, float* __restrict__ part,
+                                                         int64_t T, int32_t C) {
+    __shared__ float red[kMaxC];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t n_waves = (int64_t)gridDim.x * 4;
+    float dwacc[NV][8];
+    float wf[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c0 = (j * 64 + lane) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { dwacc[j][e] = 0.f; wf[j][e] = 0.f; }
+        if (c0 < C) widen(*reinterpret_cast<const u32x4*>(w + c0), wf[j]);
+    }
+    for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < T; row += n_waves) {
+        const __bf16* xr = x + row * C;
+        const __bf16* dyr = dy + row * C;
+        u32x4 xv[NV], dv[NV];
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c0 = (j * 64 + lane) * 8;
+            if (c0 < C) {
+                xv[j] = ld16(xr + c0);
+                dv[j] = ld16(dyr + c0);
+                float xf[8], df[8];
+                widen(xv[j], xf);
+                widen(dv[j], df);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += df[e] * wf[j][e] * xf[e];
+            }
+        }
+        dot = wave_sum(dot);
+        const float r = rstd[row];
+        const float coef = r * r * r * dot / (float)C;
+        __bf16* dxr = dx + row * C;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c0 = (j * 64 + lane) * 8;
+            if (c0 < C) {
+                float xf[8], df[8], o[8];
+                widen(xv[j], xf);
+                widen(dv[j], df);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    o[e] = df[e] * wf[j][e] * r - xf[e] * coef;
+                    dwacc[j][e] += df[e] * xf[e] * r;
+                }
+                st16(dxr + c0, narrow(o));
+            }
+        }
+    }
+    // the four waves add their terms in wave order (a fixed order: reproducible)
+    for (int wv = 0; wv < 4; ++wv) {
+        if (wave == wv) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int c0 = (j * 64 + lane) * 8;
+                if (c0 < C) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) red[c0 + e] = (wv == 0 ? 0.f : red[c0 + e]) + dwacc[j][e];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    float* prow = part + (size_t)blockIdx.x * C;
+    for (int c = threadIdx.x; c < C; c += 256) prow[c] = red[c];
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_dw_kernel(const float* __restrict__ part, __bf16* __restrict__ dw,
+                                                        int32_t n_part, int32_t C) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.f;
+    for (int i = 0; i < n_part; ++i) s += part[(size_t)i * C + c];
+    dw[c] = (__bf16)s;
+}
+
+// ------------------------------------------------------------------ rotary embedding
+// x [T, H, D]; element i of the first half of the head dim and element i of the second half are rotated
+// by the angle whose cosine and sine are cos[t, i], sin[t, i] (fp32 tables [T, D/2]); conjugate = the
+// rotation by the negative angle (the gradient).  A thread takes 8 consecutive i.  out may be x itself.
+__global__ __launch_bounds__(256) void rope_kernel(const __bf16* x, const float* __restrict__ cs,
+                                                  const float* __restrict__ sn, __bf16* out, int64_t n_vec,
+                                                  int32_t H, int32_t D, float sign) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_vec) return;
+    const int32_t vph = D / 16;  // vectors per half head
+    const int64_t th = v / vph;  // t*H + h
+    const int32_t i0 = (int32_t)(v - th * vph) * 8;
+    const int64_t t = th / H;
+    const __bf16* p1 = x + th * D + i0;
+    float a[8], b[8], c[8], s[8];
+    widen(ld16(p1), a);
+    widen(ld16(p1 + D / 2), b);
+    const float* cp = cs + t * (D / 2) + i0;
+    const float* sp_ = sn + t * (D / 2) + i0;
+    *reinterpret_cast<f32x4*>(c) = *reinterpret_cast<const f32x4*>(cp);
+    *reinterpret_cast<f32x4*>(c + 4) = *reinterpret_cast<const f32x4*>(cp + 4);
+    *reinterpret_cast<f32x4*>(s) = *reinterpret_cast<const f32x4*>(sp_);
+    *reinterpret_cast<f32x4*>(s + 4) = *reinterpret_cast<const f32x4*>(sp_ + 4);
+    float o1[8], o2[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float se = sign * s[e];
+        o1[e] = a[e] * c[e] - b[e] * se;
+        o2[e] = b[e] * c[e] + a[e] * se;
+    }
+    __bf16* q1 = out + th * D + i0;
+    st16(q1, narrow(o1));
+    st16(q1 + D / 2, narrow(o2));
+}
+
+// ------------------------------------------------------------------ SwiGLU gate
+__device__ __forceinline__ float sigmoidf(float g) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-g * kLog2e)); }
+
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const __bf16* __restrict__ g, const __bf16* __restrict__ u,
+                                                        __bf16* __restrict__ y, int64_t n_vec) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_vec) return;
+    float gf[8], uf[8], o[8];
+    widen(ld16(g + v * 8), gf);
+    widen(ld16(u + v * 8), uf);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = gf[e] * sigmoidf(gf[e]) * uf[e];
+    st16(y + v * 8, narrow(o));
+}
+
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const __bf16* __restrict__ g, const __bf16* __restrict__ u,
+                                                        const __bf16* __restrict__ dy, __bf16* __restrict__ dg,
+                                                        __bf16* __restrict__ du, int64_t n_vec) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_vec) return;
+    float gf[8], uf[8], df[8], og[8], ou[8];
+    widen(ld16(g + v * 8), gf);
+    widen(ld16(u + v * 8), uf);
+    widen(ld16(dy + v * 8), df);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float sg = sigmoidf(gf[e]);
+        og[e] = df[e] * uf[e] * sg * (1.0f + gf[e] * (1.0f - sg));
+        ou[e] = df[e] * gf[e] * sg;
+    }
+    st16(dg + v * 8, narrow(og));
+    st16(du + v * 8, narrow(ou));
+}
+
+inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+namespace sp {
+
+int32_t rmsnorm_bwd_groups(int64_t T) {
+    const int64_t g = (T + 3) / 4;
+    return (int32_t)(g < 1024 ? (g < 1 ? 1 : g) : 1024);
+}
+
+sp_status launch_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
+                             hipStream_t st) {
+    const dim3 grid(blocks_for(T, 4)), block(256);
+    const int nv = (C + 511) / 512;
+#define SP_RMS_FWD(NV) hipLaunchKernelGGL((rmsnorm_fwd_kernel<NV>), grid, block, 0, st, (const __bf16*)x, (const __bf16*)w, (__bf16*)y, rstd, T, C, eps)
+    if (nv <= 1) SP_RMS_FWD(1); else if (nv <= 2) SP_RMS_FWD(2); else if (nv <= 4) SP_RMS_FWD(4);
+    else if (nv <= 8) SP_RMS_FWD(8); else if (nv <= 16) SP_RMS_FWD(16); else return SP_ERR_UNSUPPORTED;
+#undef SP_RMS_FWD
+    return launch_status();
+}
+
+sp_status launch_rmsnorm_bwd(const void* x, const void* w, const float* rstd, const void* dy, void* dx, void* dw,
+                             float* part, int64_t T, int32_t C, hipStream_t st) {
+    const int32_t groups = rmsnorm_bwd_groups(T);
+    const dim3 grid(groups), block(256);
+    const int nv = (C + 511) / 512;
+#define SP_RMS_BWD(NV) hipLaunchKernelGGL((rmsnorm_bwd_kernel<NV>), grid, block, 0, st, (const __bf16*)x, (const __bf16*)w, rstd, (const __bf16*)dy, (__bf16*)dx, part, T, C)
+    if (nv <= 1) SP_RMS_BWD(1); else if (nv <= 2) SP_RMS_BWD(2); else if (nv <= 4) SP_RMS_BWD(4);
+    else if (nv <= 8) SP_RMS_BWD(8); else if (nv <= 16) SP_RMS_BWD(16); else return SP_ERR_UNSUPPORTED;
+#undef SP_RMS_BWD
+    if (launch_status() != SP_OK) return SP_ERR_LAUNCH;
+    hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3(blocks_for(C, 256)), dim3(256), 0, st, part, (__bf16*)dw, groups, C);
+    return launch_status();
+}
+
+sp_status launch_rope(const void* x, const float* cs, const float* sn, void* out, int64_t T, int32_t H, int32_t D,
+                      bool conjugate, hipStream_t st) {
+    const int64_t n_vec = T * H * (D / 16);
+    if ((n_vec + 255) / 256 > 0x7fffffff) return SP_ERR_SHAPE;
+    hipLaunchKernelGGL(rope_kernel, dim3(blocks_for(n_vec, 256)), dim3(256), 0, st, (const __bf16*)x, cs, sn, (__bf16*)out,
+                       n_vec, H, D, conjugate ? -1.0f : 1.0f);
+    return launch_status();
+}
+
+sp_status launch_swiglu_fwd(const void* g, const void* u, void* y, int64_t n, hipStream_t st) {
+    const int64_t n_vec = n / 8;
+    if ((n_vec + 255) / 256 > 0x7fffffff) return SP_ERR_SHAPE;
+    hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(blocks_for(n_vec, 256)), dim3(256), 0, st, (const __bf16*)g, (const __bf16*)u,
+                       (__bf16*)y, n_vec);
+    return launch_status();
+}
+
+sp_status launch_swiglu_bwd(const void* g, const void* u, const void* dy, void* dg, void* du, int64_t n, hipStream_t st) {
+    const int64_t n_vec = n / 8;
+    if ((n_vec + 255) / 256 > 0x7fffffff) return SP_ERR_SHAPE;
+    hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(blocks_for(n_vec, 256)), dim3(256), 0, st, (const __bf16*)g, (const __bf16*)u,
+                       (const __bf16*)dy, (__bf16*)dg, (__bf16*)du, n_vec);
+    return launch_status();
+}
+
+}  // namespace sp

@@ -284,4 +284,67 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     return sp::launch_attn_bwd(a, s);
 }
 
+// ------------------------------------------------------------------ pointwise operators outside attention
+size_t sp_rmsnorm_bwd_workspace_bytes(int64_t T, int32_t C) {
+    if (T <= 0 || C <= 0 || C % 8 != 0 || C > 8192) return 0;
+    return align_up((size_t)sp::rmsnorm_bwd_groups(T) * (size_t)C * sizeof(float), 256);
+}
+
+sp_status sp_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
+                         void* hip_stream) {
+    if (T < 0 || C < 0 || !(eps >= 0.f)) return SP_ERR_SHAPE;
+    if (C % 8 != 0 || C > 8192) return SP_ERR_UNSUPPORTED;
+    if (T == 0 || C == 0) return SP_OK;
+    if (!x || !w || !y || !rstd) return SP_ERR_NULL;
+    if (!sp::aligned16(x) || !sp::aligned16(w) || !sp::aligned16(y) || !sp::aligned16(rstd)) return SP_ERR_ALIGN;
+    if ((T + 3) / 4 > 0x7fffffff) return SP_ERR_SHAPE;
+    return sp::launch_rmsnorm_fwd(x, w, y, rstd, T, C, eps, (hipStream_t)hip_stream);
+}
+
+sp_status sp_rmsnorm_bwd(const void* x, const void* w, const float* rstd, const void* dy, void* dx, void* dw,
+                         void* workspace, size_t workspace_bytes, int64_t T, int32_t C, void* hip_stream) {
+    if (T < 0 || C < 0) return SP_ERR_SHAPE;
+    if (C % 8 != 0 || C > 8192) return SP_ERR_UNSUPPORTED;
+    if (C == 0) return SP_OK;
+    if (!x || !w || !rstd || !dy || !dx || !dw || !workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {x, w, rstd, dy, dx, dw, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if (T == 0) return SP_ERR_SHAPE;  // dw of an empty batch is not defined by a launch-free call
+    if (workspace_bytes < sp_rmsnorm_bwd_workspace_bytes(T, C)) return SP_ERR_WORKSPACE;
+    return sp::launch_rmsnorm_bwd(x, w, rstd, dy, dx, dw, (float*)workspace, T, C, (hipStream_t)hip_stream);
+}
+
+sp_status sp_rope(const void* x, const float* cos_table, const float* sin_table, void* out, int64_t T, int32_t H,
+                  int32_t D, int32_t conjugate, void* hip_stream) {
+    if (T < 0 || H < 0 || D < 0) return SP_ERR_SHAPE;
+    if (D % 16 != 0) return SP_ERR_UNSUPPORTED;
+    if (T == 0 || H == 0 || D == 0) return SP_OK;
+    if (!x || !cos_table || !sin_table || !out) return SP_ERR_NULL;
+    if (!sp::aligned16(x) || !sp::aligned16(cos_table) || !sp::aligned16(sin_table) || !sp::aligned16(out))
+        return SP_ERR_ALIGN;
+    return sp::launch_rope(x, cos_table, sin_table, out, T, H, D, conjugate != 0, (hipStream_t)hip_stream);
+}
+
+sp_status sp_swiglu_fwd(const void* g, const void* u, void* y, int64_t n, void* hip_stream) {
+    if (n < 0) return SP_ERR_SHAPE;
+    if (n % 8 != 0) return SP_ERR_UNSUPPORTED;
+    if (n == 0) return SP_OK;
+    if (!g || !u || !y) return SP_ERR_NULL;
+    if (!sp::aligned16(g) || !sp::aligned16(u) || !sp::aligned16(y)) return SP_ERR_ALIGN;
+    return sp::launch_swiglu_fwd(g, u, y, n, (hipStream_t)hip_stream);
+}
+
+sp_status sp_swiglu_bwd(const void* g, const void* u, const void* dy, void* dg, void* du, int64_t n,
+                        void* hip_stream) {
+    if (n < 0) return SP_ERR_SHAPE;
+    if (n % 8 != 0) return SP_ERR_UNSUPPORTED;
+    if (n == 0) return SP_OK;
+    if (!g || !u || !dy || !dg || !du) return SP_ERR_NULL;
+    const void* ptrs[] = {g, u, dy, dg, du};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    return sp::launch_swiglu_bwd(g, u, dy, dg, du, n, (hipStream_t)hip_stream);
+}
+
 }  // extern "C"

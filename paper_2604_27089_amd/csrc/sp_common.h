@@ -87,6 +87,17 @@ inline size_t dkdv_part_bytes(int64_t B, int64_t S, int32_t Hkv, int32_t D, int3
     return nsplit > 1 ? (size_t)2 * nsplit * B * S * Hkv * D * sizeof(float) : 0;
 }
 
+// pointwise operators outside attention (pointwise.hip)
+sp_status launch_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
+                             hipStream_t st);
+sp_status launch_rmsnorm_bwd(const void* x, const void* w, const float* rstd, const void* dy, void* dx, void* dw,
+                             float* part, int64_t T, int32_t C, hipStream_t st);
+int32_t rmsnorm_bwd_groups(int64_t T);  // partial rows of dw the backward writes to its workspace
+sp_status launch_rope(const void* x, const float* cs, const float* sn, void* out, int64_t T, int32_t H, int32_t D,
+                      bool conjugate, hipStream_t st);
+sp_status launch_swiglu_fwd(const void* g, const void* u, void* y, int64_t n, hipStream_t st);
+sp_status launch_swiglu_bwd(const void* g, const void* u, const void* dy, void* dg, void* du, int64_t n, hipStream_t st);
+
 // row pitch of the per-row backward scalars
 inline int32_t aux_pitch(int64_t S) { return (int32_t)((S + 63) / 64 * 64 + 64); }
 

@@ -92,6 +92,29 @@ def test_attention_argument_errors():
     assert sb(*args, need8, 1, 500, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_UNSUPPORTED
 
 
+def test_pointwise_argument_errors():
+    L = sp.lib()
+    assert L.sp_rmsnorm_fwd(A(1), A(2), A(3), A(4), 4, 4100, 1e-5, None) == sp.SP_ERR_UNSUPPORTED   # C % 8
+    assert L.sp_rmsnorm_fwd(A(1), A(2), A(3), A(4), 4, 16384, 1e-5, None) == sp.SP_ERR_UNSUPPORTED  # C > 8192
+    assert L.sp_rmsnorm_fwd(A(1), A(2), A(3), A(4), -1, 64, 1e-5, None) == sp.SP_ERR_SHAPE
+    assert L.sp_rmsnorm_fwd(A(1), A(2), A(3), A(4), 4, 64, -1.0, None) == sp.SP_ERR_SHAPE
+    assert L.sp_rmsnorm_fwd(None, A(2), A(3), A(4), 4, 64, 1e-5, None) == sp.SP_ERR_NULL
+    assert L.sp_rmsnorm_fwd(None, None, None, None, 0, 64, 1e-5, None) == sp.SP_OK
+    need = sp.sp_rmsnorm_bwd_workspace_bytes(4096, 4096)
+    assert need >= 1024 * 4096 * 4 and sp.sp_rmsnorm_bwd_workspace_bytes(4096, 12) == 0
+    a7 = [A(i) for i in range(1, 8)]
+    assert L.sp_rmsnorm_bwd(*a7, need - 1, 4096, 4096, None) == sp.SP_ERR_WORKSPACE
+    assert L.sp_rmsnorm_bwd(*a7[:6], None, need, 4096, 4096, None) == sp.SP_ERR_NULL
+    assert L.sp_rope(A(1), A(2), A(3), A(4), 8, 4, 24, 0, None) == sp.SP_ERR_UNSUPPORTED  # D % 16
+    assert L.sp_rope(A(1), None, A(3), A(4), 8, 4, 64, 0, None) == sp.SP_ERR_NULL
+    assert L.sp_rope(A(1), A(2), A(3), ctypes.c_void_p(0x4008), 8, 4, 64, 1, None) == sp.SP_ERR_ALIGN
+    assert L.sp_rope(None, None, None, None, 0, 4, 64, 0, None) == sp.SP_OK
+    assert L.sp_swiglu_fwd(A(1), A(2), A(3), 12, None) == sp.SP_ERR_UNSUPPORTED           # n % 8
+    assert L.sp_swiglu_fwd(A(1), A(2), None, 16, None) == sp.SP_ERR_NULL
+    assert L.sp_swiglu_bwd(A(1), A(2), A(3), A(4), A(5), -8, None) == sp.SP_ERR_SHAPE
+    assert L.sp_swiglu_bwd(None, None, None, None, None, 0, None) == sp.SP_OK
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(sp, "_lib", None)
     monkeypatch.setattr(sp, "LIB_PATH", "/nonexistent/libsp_hotpath.so")
