@@ -321,6 +321,34 @@ def main():
             t = time_fn(folded, max(3, args.steps // 2), 1)
             detail["seqlayout_step"] = {"ms": t, "fwd_bwd_tflops": (fl_fwd + fl_bwd) / (t * 1e-3) / 1e12}
 
+        # pointwise operators outside attention on the 8B-shaped token shard [16384 tokens, model dim 4096,
+        # 32 heads of 128, MLP width 14336]: algorithmic bytes (every operand read once, every result written
+        # once) over time, against the HBM peak
+        if not args.no_other_shards:
+            Tt, Cc, Hh, Ff = S_l, 4096, 32, 14336
+            px, pdy = (torch.empty((Tt, Cc), **bf).normal_() for _ in range(2))
+            pw = torch.empty((Cc,), **bf).normal_()
+            py, prs = sp.sp_rmsnorm_fwd(px, pw, 1e-5)
+            pdx, pdw = torch.empty_like(px), torch.empty_like(pw)
+            pws = torch.empty(sp.sp_rmsnorm_bwd_workspace_bytes(Tt, Cc), dtype=torch.uint8, device=dev)
+            rq = torch.empty((Tt, Hh, D), **bf).normal_()
+            rout = torch.empty_like(rq)
+            tab = torch.empty((Tt, D // 2), dtype=torch.float32, device=dev).uniform_(-1, 1)
+            sg, su, sdy = (torch.empty((Tt, Ff), **bf).normal_() for _ in range(3))
+            sy, sdg, sdu = torch.empty_like(sg), torch.empty_like(sg), torch.empty_like(sg)
+            e2 = 2.0
+            ops = [
+                ("rmsnorm_fwd", lambda: sp.sp_rmsnorm_fwd(px, pw, 1e-5, y=py, rstd=prs), e2 * 2 * Tt * Cc),
+                ("rmsnorm_bwd", lambda: sp.sp_rmsnorm_bwd(px, pw, prs, pdy, dx=pdx, dw=pdw, workspace=pws), e2 * 3 * Tt * Cc),
+                ("rope", lambda: sp.sp_rope(rq, tab, tab, out=rout), e2 * 2 * Tt * Hh * D + 8.0 * Tt * (D // 2)),
+                ("swiglu_fwd", lambda: sp.sp_swiglu_fwd(sg, su, y=sy), e2 * 3 * Tt * Ff),
+                ("swiglu_bwd", lambda: sp.sp_swiglu_bwd(sg, su, sdy, dg=sdg, du=sdu), e2 * 5 * Tt * Ff),
+            ]
+            detail["pointwise"] = {"shard": f"T={Tt} C={Cc} H={Hh} D={D} F={Ff} bf16", "peak_GBps": HBM_PEAK_GBPS}
+            for name, fn, nbytes in ops:
+                t = time_fn(fn, 20, 3)
+                detail["pointwise"][name] = {"us": t * 1e3, "bytes": nbytes, "GBps": nbytes / t / 1e6}
+            del px, pdy, py, pdx, rq, rout, sg, su, sdy, sy, sdg, sdu, pws
         # What the vendor library's plain bf16 GEMM reaches on this machine at the same power cap: a practical
         # ceiling for matrix work, like the device copy is for the re-layout.
         ga = torch.empty((8192, 8192), **bf).normal_()

@@ -21,7 +21,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kMaxC = 8192;  // widest row the RMS-norm kernels keep in registers (16 vectors of 8 per lane)
 
 __device__ __forceinline__ void widen(const u32x4& v, float (&f)[8]) {
     const bf16x8 b = __builtin_bit_cast(bf16x8, v);
@@ -56,122 +55,143 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const __bf16* __restri
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= T) return;
     const __bf16* xr = x + row * C;
+    // loads are unconditional (columns past the row's end re-read its last vector and count as zeros), so
+    // that all of a lane's loads are in flight together
     u32x4 xv[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c0 = (j * 64 + lane) * 8;
+        xv[j] = ld16(xr + (c0 < C ? c0 : C - 8));
+    }
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int c0 = (j * 64 + lane) * 8;
-        if (c0 < C) {
-            xv[j] = ld16(xr + c0);
-            float f[8];
-            widen(xv[j], f);
+        float f[8];
+        widen(xv[j], f);
+        float s8 = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
-        }
+        for (int e = 0; e < 8; ++e) s8 += f[e] * f[e];
+        ss += c0 < C ? s8 : 0.f;
     }
     ss = wave_sum(ss);
     const float r = 1.0f / sqrtf(ss / (float)C + eps);
     if (lane == 0) rstd[row] = r;
     __bf16* yr = y + row * C;
+    u32x4 wv[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int c0 = (j * 64 + lane) * 8;
-        if (c0 < C) {
-            float f[8], g[8];
-            widen(xv[j], f);
-            widen(*reinterpret_cast<const u32x4*>(w + c0), g);
+        wv[j] = *reinterpret_cast<const u32x4*>(w + (c0 < C ? c0 : C - 8));
+    }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
-            st16(yr + c0, narrow(f));
-        }
+    for (int j = 0; j < NV; ++j) {
+        const int c0 = (j * 64 + lane) * 8;
+        float f[8], g[8];
+        widen(xv[j], f);
+        widen(wv[j], g);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
+        if (c0 < C) st16(yr + c0, narrow(f));
     }
 }
 
 // ------------------------------------------------------------------ RMS norm, backward
 //   g = dy * w,  dx = g * rstd - x * rstd^3 * (sum_c g x) / C,  dw = sum_t dy * x * rstd
-// One wave per row, rows dealt round-robin to the waves of a persistent grid; a lane keeps the dw terms
-// of its columns in registers over all its rows, the four waves of a workgroup add theirs through LDS
-// and the workgroup writes one fp32 partial row; rmsnorm_dw_kernel adds the partial rows in a fixed order.
-template <int NV>
+// One workgroup per row, rows dealt round-robin to a fixed number of workgroups; thread t owns the 8-column
+// vectors number t, t+256, ... (NVT of them, C <= 2048*NVT) and keeps their dw terms in registers over all its
+// rows, so a workgroup's partial row of dw needs no reduction; the row's sum_c g x goes wave sums -> LDS ->
+// every thread adds the four.  rmsnorm_dw_kernel adds the partial rows in a fixed order.
+template <int NVT>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ w,
                                                          const float* __restrict__ rstd, const __bf16* __restrict__ dy,
                                                          __bf16* __restrict__ dx, float* __restrict__ part,
                                                          int64_t T, int32_t C) {
-    __shared__ float red[kMaxC];
+    __shared__ float wsum[2][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t n_waves = (int64_t)gridDim.x * 4;
-    float dwacc[NV][8];
-    float wf[NV][8];
+    float dwacc[NVT][8];
+    u32x4 wv[NVT];  // w of the thread's columns (zeros past the row's end, which also zeroes every term there)
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-        const int c0 = (j * 64 + lane) * 8;
+    for (int j = 0; j < NVT; ++j) {
+        const int c0 = (j * 256 + (int)threadIdx.x) * 8;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { dwacc[j][e] = 0.f; wf[j][e] = 0.f; }
-        if (c0 < C) widen(*reinterpret_cast<const u32x4*>(w + c0), wf[j]);
+        for (int e = 0; e < 8; ++e) dwacc[j][e] = 0.f;
+        wv[j] = *reinterpret_cast<const u32x4*>(w + (c0 < C ? c0 : C - 8));
+        if (c0 >= C) wv[j] = u32x4{0, 0, 0, 0};
     }
-    for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < T; row += n_waves) {
+    int par = 0;
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, par ^= 1) {
         const __bf16* xr = x + row * C;
         const __bf16* dyr = dy + row * C;
-        u32x4 xv[NV], dv[NV];
+        u32x4 xv[NVT], dv[NVT];
+#pragma unroll
+        for (int j = 0; j < NVT; ++j) {
+            const int c0 = (j * 256 + (int)threadIdx.x) * 8;
+            const int cc = c0 < C ? c0 : C - 8;
+            xv[j] = ld16(xr + cc);
+            dv[j] = ld16(dyr + cc);
+        }
+        const float r = rstd[row];
         float dot = 0.f;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int c0 = (j * 64 + lane) * 8;
-            if (c0 < C) {
-                xv[j] = ld16(xr + c0);
-                dv[j] = ld16(dyr + c0);
-                float xf[8], df[8];
-                widen(xv[j], xf);
-                widen(dv[j], df);
+        for (int j = 0; j < NVT; ++j) {
+            float xf[8], df[8], wf[8];
+            widen(xv[j], xf);
+            widen(dv[j], df);
+            widen(wv[j], wf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot += df[e] * wf[j][e] * xf[e];
-            }
+            for (int e = 0; e < 8; ++e) dot += df[e] * wf[e] * xf[e];
         }
         dot = wave_sum(dot);
-        const float r = rstd[row];
+        if (lane == 0) wsum[par][wave] = dot;
+        __syncthreads();  // the other parity's slots are free again: everybody read them before this barrier
+        dot = (wsum[par][0] + wsum[par][1]) + (wsum[par][2] + wsum[par][3]);
         const float coef = r * r * r * dot / (float)C;
         __bf16* dxr = dx + row * C;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int c0 = (j * 64 + lane) * 8;
-            if (c0 < C) {
-                float xf[8], df[8], o[8];
-                widen(xv[j], xf);
-                widen(dv[j], df);
+        for (int j = 0; j < NVT; ++j) {
+            const int c0 = (j * 256 + (int)threadIdx.x) * 8;
+            float xf[8], df[8], wf[8], o[8];
+            widen(xv[j], xf);
+            widen(dv[j], df);
+            widen(wv[j], wf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    o[e] = df[e] * wf[j][e] * r - xf[e] * coef;
-                    dwacc[j][e] += df[e] * xf[e] * r;
-                }
-                st16(dxr + c0, narrow(o));
+            for (int e = 0; e < 8; ++e) {
+                o[e] = df[e] * wf[e] * r - xf[e] * coef;
+                dwacc[j][e] += df[e] * xf[e] * r;
             }
+            if (c0 < C) st16(dxr + c0, narrow(o));
         }
-    }
-    // the four waves add their terms in wave order (a fixed order: reproducible)
-    for (int wv = 0; wv < 4; ++wv) {
-        if (wave == wv) {
-#pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                const int c0 = (j * 64 + lane) * 8;
-                if (c0 < C) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) red[c0 + e] = (wv == 0 ? 0.f : red[c0 + e]) + dwacc[j][e];
-                }
-            }
-        }
-        __syncthreads();
     }
     float* prow = part + (size_t)blockIdx.x * C;
-    for (int c = threadIdx.x; c < C; c += 256) prow[c] = red[c];
+#pragma unroll
+    for (int j = 0; j < NVT; ++j) {
+        const int c0 = (j * 256 + (int)threadIdx.x) * 8;
+        if (c0 < C) {
+            *reinterpret_cast<f32x4*>(prow + c0) = f32x4{dwacc[j][0], dwacc[j][1], dwacc[j][2], dwacc[j][3]};
+            *reinterpret_cast<f32x4*>(prow + c0 + 4) = f32x4{dwacc[j][4], dwacc[j][5], dwacc[j][6], dwacc[j][7]};
+        }
+    }
 }
 
+// dw[c] = sum of the partial rows, in a fixed order: a block takes 16 columns, its 16 thread rows take every
+// sixteenth partial row each, and their sums are added in thread-row order through LDS
 __global__ __launch_bounds__(256) void rmsnorm_dw_kernel(const float* __restrict__ part, __bf16* __restrict__ dw,
                                                         int32_t n_part, int32_t C) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float red[16][17];
+    const int cl = threadIdx.x & 15, pl = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + cl;
     float s = 0.f;
-    for (int i = 0; i < n_part; ++i) s += part[(size_t)i * C + c];
-    dw[c] = (__bf16)s;
+    if (c < C)
+        for (int i = pl; i < n_part; i += 16) s += part[(size_t)i * C + c];
+    red[pl][cl] = s;
+    __syncthreads();
+    if (pl == 0 && c < C) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += red[k][cl];
+        dw[c] = (__bf16)t;
+    }
 }
 
 // ------------------------------------------------------------------ rotary embedding
@@ -249,10 +269,7 @@ inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1)
 
 namespace sp {
 
-int32_t rmsnorm_bwd_groups(int64_t T) {
-    const int64_t g = (T + 3) / 4;
-    return (int32_t)(g < 1024 ? (g < 1 ? 1 : g) : 1024);
-}
+int32_t rmsnorm_bwd_groups(int64_t T) { return (int32_t)(T < 1024 ? (T < 1 ? 1 : T) : 1024); }
 
 sp_status launch_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
                              hipStream_t st) {
@@ -269,13 +286,12 @@ sp_status launch_rmsnorm_bwd(const void* x, const void* w, const float* rstd, co
                              float* part, int64_t T, int32_t C, hipStream_t st) {
     const int32_t groups = rmsnorm_bwd_groups(T);
     const dim3 grid(groups), block(256);
-    const int nv = (C + 511) / 512;
+    const int nv = (C + 2047) / 2048;
 #define SP_RMS_BWD(NV) hipLaunchKernelGGL((rmsnorm_bwd_kernel<NV>), grid, block, 0, st, (const __bf16*)x, (const __bf16*)w, rstd, (const __bf16*)dy, (__bf16*)dx, part, T, C)
-    if (nv <= 1) SP_RMS_BWD(1); else if (nv <= 2) SP_RMS_BWD(2); else if (nv <= 4) SP_RMS_BWD(4);
-    else if (nv <= 8) SP_RMS_BWD(8); else if (nv <= 16) SP_RMS_BWD(16); else return SP_ERR_UNSUPPORTED;
+    if (nv <= 1) SP_RMS_BWD(1); else if (nv <= 2) SP_RMS_BWD(2); else if (nv <= 4) SP_RMS_BWD(4); else return SP_ERR_UNSUPPORTED;
 #undef SP_RMS_BWD
     if (launch_status() != SP_OK) return SP_ERR_LAUNCH;
-    hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3(blocks_for(C, 256)), dim3(256), 0, st, part, (__bf16*)dw, groups, C);
+    hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3(blocks_for(C, 16)), dim3(256), 0, st, part, (__bf16*)dw, groups, C);
     return launch_status();
 }
 
