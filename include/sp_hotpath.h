@@ -51,7 +51,7 @@ typedef enum {
 /* Static, human-readable name of a status code.  Never NULL. */
 const char* sp_status_str(sp_status s);
 
-/* Version of this ABI (bumped on any signature change). */
+/* Version of this ABI (bumped on any signature change and when a workspace requirement grows). */
 int32_t sp_abi_version(void);
 
 /* ---------------------------------------------------------------------------

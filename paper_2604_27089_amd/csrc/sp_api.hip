@@ -73,7 +73,7 @@ const char* sp_status_str(sp_status s) {
     return "SP_ERR_?: unknown status";
 }
 
-int32_t sp_abi_version(void) { return 1; }
+int32_t sp_abi_version(void) { return 2; }
 
 sp_status sp_pack_seq_to_head(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
                               int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream) {

@@ -70,6 +70,23 @@ def test_bwd_scale_determinism_and_invariants():
     assert np.abs(got - want).max() <= 0.02 * np.abs(want).max() + 0.3
 
 
+def test_bwd_shared_key_tiles_are_reproducible():
+    """Several workgroups share each key tile here (fp32 partial sums added in a fixed order): two runs, and a
+    run into a workspace full of garbage, give the same bits."""
+    S, Hq, Hkv, D = 2304, 4, 1, 128
+    q, k, v, do = synth.attn_inputs(12, S, Hq, Hkv, D)
+    qd, kd, vd, dod = (dev_bf16(t) for t in (q, k, v, do))
+    o, lse = sp.sp_attn_fwd(qd, kd, vd)
+    ws = torch.empty(sp.sp_attn_bwd_workspace_bytes(1, S, Hq, Hkv, D), dtype=torch.uint8, device="cuda")
+    a = sp.sp_attn_bwd(qd, kd, vd, o, lse, dod, workspace=ws)
+    a = tuple(t.clone() for t in a)
+    ws.random_(0, 256)
+    b = sp.sp_attn_bwd(qd, kd, vd, o, lse, dod, workspace=ws)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
 def sparse_rows(S, n, seed):
     rng = np.random.default_rng(seed)
     fixed = [0, 1, 63, 64, 127, 128, S // 2, S - 129, S - 128, S - 64, S - 2, S - 1]
