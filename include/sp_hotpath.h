@@ -176,6 +176,57 @@ sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, con
                                 void* hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * One step of a ring schedule (the second sequence-parallel scheme the paper
+ * measures, Section 4 baselines and Section 4.1: the sequence stays sharded and
+ * key/value blocks are passed from device to device in p steps).  Per arriving
+ * block a device computes the attention of its query block against that block
+ * and merges it into a running result; in the backward pass it computes the
+ * block pair's share of the gradients.
+ *
+ *   q, o, dO, dq [B, Sq, Hq, D]; k, v, dk, dv [B, Skv, Hkv, D]   bf16
+ *   lse [B, Hq, Sq]                                               fp32
+ *
+ * Query row i sees keys j <= i + causal_offset.  With the query block starting
+ * at global position a and the key block at global position c, causal
+ * attention over the whole sequence is causal_offset = a - c: 0 for the
+ * diagonal block, anything >= Skv - 1 hides nothing (a block from the past);
+ * blocks from the future are not computed at all.  Required: causal_offset >= 0
+ * and Skv <= Sq + causal_offset (every key is seen by some row); SP_ERR_SHAPE
+ * otherwise.  sp_attn_fwd is the case Skv = Sq, causal_offset = 0, bit for bit.
+ *
+ * sp_attn_block_fwd: o, lse of the block alone (the softmax runs over the
+ *   visible keys of this block only).
+ * sp_attn_merge: folds a block's (o_blk bf16, lse_blk) into the running
+ *   (o_acc fp32 [B, S, Hq, D], lse_acc fp32 [B, Hq, S]), in place:
+ *     lse = log(e^lse_acc + e^lse_blk),
+ *     o   = e^(lse_acc - lse) o_acc + e^(lse_blk - lse) o_blk.
+ *   The caller starts from o_acc = 0, lse_acc = -inf.  If o_out is not NULL the
+ *   merged O is also written there in bf16 (pass it with the last block).
+ * sp_attn_block_bwd: dq, dk, dv = this block pair's shares (bf16; the caller
+ *   adds the dq shares over key blocks and the dk, dv shares over query
+ *   blocks).  o and lse are the FINAL (merged) ones of the query rows, dO the
+ *   gradient of the final O.  `stages` as in sp_attn_bwd_stages: the delta
+ *   stage depends on o, dO, lse only, so a caller looping over key blocks may
+ *   run it once (SP_BWD_STAGE_ALL on the first block) and pass
+ *   SP_BWD_STAGE_DKDV | SP_BWD_STAGE_DQ with the same workspace afterwards.
+ *   Workspace: sp_attn_block_bwd_workspace_bytes (0 for invalid extents).
+ * Outputs are fully overwritten; nothing is allocated; same error behaviour as
+ * the entry points above.
+ * ------------------------------------------------------------------------- */
+sp_status sp_attn_block_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
+                            int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D,
+                            int64_t causal_offset, float softmax_scale, void* hip_stream);
+sp_status sp_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, const float* lse_blk, void* o_out,
+                        int64_t B, int64_t S, int32_t Hq, int32_t D, void* hip_stream);
+size_t sp_attn_block_bwd_workspace_bytes(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv,
+                                         int32_t D);
+sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                            const void* dO, void* dq, void* dk, void* dv, void* workspace,
+                            size_t workspace_bytes, int64_t B, int64_t Sq, int64_t Skv, int32_t Hq,
+                            int32_t Hkv, int32_t D, int64_t causal_offset, float softmax_scale,
+                            int32_t stages, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Packed variable-length documents (not in the paper; the block-diagonal form
  * of the same operator, as long-context training batches are usually packed).
  *

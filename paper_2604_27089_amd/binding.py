@@ -24,6 +24,7 @@ EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
     "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
     "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
+    "sp_attn_block_fwd", "sp_attn_merge", "sp_attn_block_bwd_workspace_bytes", "sp_attn_block_bwd",
     "sp_rmsnorm_bwd_workspace_bytes", "sp_rmsnorm_fwd", "sp_rmsnorm_bwd", "sp_rope", "sp_swiglu_fwd", "sp_swiglu_bwd",
 )
 
@@ -67,6 +68,14 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_fwd_seqlayout.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, f32, vp]
     L.sp_attn_bwd_seqlayout.restype = c.c_int
     L.sp_attn_bwd_seqlayout.argtypes = [vp] * 10 + [sz, i64, i64, i32, i32, i32, i32, f32, vp]
+    L.sp_attn_block_fwd.restype = c.c_int
+    L.sp_attn_block_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i64, f32, vp]
+    L.sp_attn_merge.restype = c.c_int
+    L.sp_attn_merge.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp]
+    L.sp_attn_block_bwd_workspace_bytes.restype = sz
+    L.sp_attn_block_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32]
+    L.sp_attn_block_bwd.restype = c.c_int
+    L.sp_attn_block_bwd.argtypes = [vp] * 10 + [sz, i64, i64, i64, i32, i32, i32, i64, f32, i32, vp]
     L.sp_attn_varlen_fwd.restype = c.c_int
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
@@ -212,6 +221,47 @@ def sp_attn_bwd_seqlayout(q, k, v, o, lse, do, P: int, softmax_scale: float = 0.
     _check(lib().sp_attn_bwd_seqlayout(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
                                        _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S_l, Hq, Hkv,
                                        D, P, float(softmax_scale), _stream(stream)), "sp_attn_bwd_seqlayout")
+    return dq, dk, dv
+
+
+def sp_attn_block_fwd(q, k, v, causal_offset: int, softmax_scale: float = 0.0, o=None, lse=None, stream=None):
+    """q [B,Sq,Hq,D], k,v [B,Skv,Hkv,D]; row i sees keys j <= i + causal_offset -> (o, lse [B,Hq,Sq])."""
+    B, Sq, Hq, D = q.shape
+    Skv, Hkv = k.shape[1], k.shape[2]
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device=q.device) if lse is None else lse
+    _check(lib().sp_attn_block_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Sq, Skv, Hq, Hkv, D,
+                                   int(causal_offset), float(softmax_scale), _stream(stream)), "sp_attn_block_fwd")
+    return o, lse
+
+
+def sp_attn_merge(o_acc, lse_acc, o_blk, lse_blk, o_out=None, stream=None):
+    """Folds (o_blk bf16, lse_blk) into the running (o_acc fp32 [B,S,Hq,D], lse_acc fp32 [B,Hq,S]) in place;
+    also writes the merged O as bf16 into o_out if given."""
+    B, S, Hq, D = o_acc.shape
+    _check(lib().sp_attn_merge(_ptr(o_acc), _ptr(lse_acc), _ptr(o_blk), _ptr(lse_blk), _ptr(o_out), B, S, Hq, D,
+                               _stream(stream)), "sp_attn_merge")
+    return o_acc, lse_acc
+
+
+def sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D) -> int:
+    return int(lib().sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D))
+
+
+def sp_attn_block_bwd(q, k, v, o, lse, do, causal_offset: int, softmax_scale: float = 0.0, dq=None, dk=None,
+                      dv=None, workspace=None, stages: int = SP_BWD_STAGE_ALL, stream=None):
+    """This block pair's shares (dq, dk, dv), from the final o, lse of the query rows."""
+    B, Sq, Hq, D = q.shape
+    Skv, Hkv = k.shape[1], k.shape[2]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    if workspace is None:
+        workspace = _workspace(sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D), q.device)
+    _check(lib().sp_attn_block_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq), _ptr(dk),
+                                   _ptr(dv), _ptr(workspace), workspace.numel(), B, Sq, Skv, Hq, Hkv, D,
+                                   int(causal_offset), float(softmax_scale), int(stages), _stream(stream)),
+           "sp_attn_block_bwd")
     return dq, dk, dv
 
 

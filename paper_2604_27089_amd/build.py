@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsp_hotpath.so")
-SOURCES = ["sp_api.hip", "relayout.hip", "doc_bounds.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_dkdv.hip", "attn_bwd_dq.hip", "pointwise.hip"]
+SOURCES = ["sp_api.hip", "relayout.hip", "doc_bounds.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_bwd_dkdv.hip", "attn_bwd_dq.hip", "attn_merge.hip", "pointwise.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-command-line-argument", "-Wno-unused-parameter",
          # keep the compiler from forming packed-fp32 VALU instructions

@@ -50,10 +50,10 @@ struct DkdvParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* dO;
     const float* aux;  // per 32-row tile: 32 x -LSE/scale then 32 x -Delta; [B*Hq, S_pad/32, 2, 32]
     __bf16* dk; __bf16* dv;
-    float* part;  // nsplit > 1: fp32 partial sums, [2 (dK unscaled, dV)][nsplit][B, S, Hkv, D]
+    float* part;  // nsplit > 1: fp32 partial sums, [2 (dK unscaled, dV)][nsplit][B, Skv, Hkv, D]
     const int32_t* row_hi;
     RowMap qmap, kvmap;
-    int32_t S, S_pad, Hq, Hkv, G, n_ktiles, nsplit;
+    int32_t S, Skv, off, S_pad, Hq, Hkv, G, n_ktiles, nsplit;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale, scale_log2;
 };
 
@@ -84,9 +84,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int nsplit = SPLIT ? p.nsplit : 1;
     const int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x, split = SPLIT ? blockIdx.x % nsplit : 0;
     const int g = blockIdx.y, b = blockIdx.z;
-    const int S = p.S;
-    const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
-    const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
+    const int S = p.S, Skv = p.Skv;
+    const __bf16* kb = p.k + ((size_t)b * Skv * p.Hkv + g) * D;
+    const __bf16* vb = p.v + ((size_t)b * Skv * p.Hkv + g) * D;
 
     const int j0 = jt * BNK;
     const int wkey0 = j0 + KPW * wave;  // first key of this wave
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
     for (int kbk = 0; kbk < 2; ++kbk) {
         const int key = wkey0 + 32 * kbk + lo;
-        const int key_c = key < S ? key : S - 1;
+        const int key_c = key < Skv ? key : Skv - 1;
 #pragma unroll
         for (int kk = 0; kk < NS; ++kk) {
             kreg[kbk][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + p.kvmap.off(key_c) + 16 * kk + 8 * hi));
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
             tb[half][db] = sm + tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
     const uint32_t ab = sm + AUX + wave * AUX_W + 16 * hi;  // per-row scalars: rows 8*g4 + 4*hi .. +3
 
-    const int it_begin = j0 / BMQ;                   // tile holding the first key's own row
+    const int it_begin = (j0 > p.off ? j0 - p.off : 0) / BMQ;  // tile holding the first row that sees the first key
     const int it_end = (wg_hi_max + BMQ - 1) / BMQ;  // exclusive
     const int n_it = it_end - it_begin;
     // Steps are (head in group, row tile) pairs, heads ascending, rows descending inside a head.  The
@@ -211,14 +211,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     // ---- prologue: V (resident), a finite stand-in tile for the deferred dK of "step -1", steps 0 and 1 ----
     int cur_it = it_first;    // row tile of the step being computed
     int step_no = 0;          // its number (the step count is padded to a multiple of four: steps >= total are not real)
-    // row tiles whose S' needs masking: those reaching down into the wave's keys, and those reaching the end
-    // of the first key's document (dense: the end of the sequence)
-    const int it_mask_lo = (wkey0 + KPW - 2) / BMQ;
+    // row tiles whose S' needs masking: those holding a row that does not see the wave's last key, and those
+    // reaching the end of the first key's document (dense: the end of the sequence)
+    const int last_hidden = wkey0 + KPW - 2 - p.off;  // last row that does not see all the wave's keys
+    const int it_mask_lo = last_hidden >= 0 ? last_hidden / BMQ : -1;
     const int it_mask_hi = (wave_hi_min - 31 + BMQ - 1) / BMQ;
     {
         TileDma<D, BNK, kWaves> vdma;
         vdma.init(wave, lane, p.kvmap.row_stride);
-        vdma.issue(vb + p.kvmap.off(j0), S - 1 - j0, reinterpret_cast<__bf16*>(smem + VS), wave);
+        vdma.issue(vb + p.kvmap.off(j0), Skv - 1 - j0, reinterpret_cast<__bf16*>(smem + VS), wave);
         static_for<1, PW + 1>([&](auto K) { issue_load(K, 3); });  // Q rows of step 0 again, as the stand-in
         static_for<0, GROUP>([&](auto K) { issue_load(K, 0); });
         advance_load();
@@ -400,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int row = q0 + 8 * (r / 4) + 4 * (int)(__lane_id() >> 5) + (r % 4);
-                                const bool vis = real && row >= key && row < key_hi;
+                                const bool vis = real && row + p.off >= key && row < key_hi;
                                 sacc[kbk][r] = vis ? sacc[kbk][r] : -__builtin_inff();
                             }
                         }
@@ -483,7 +484,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     // ---- write dK and dV: accumulator rows = keys, column = d ----
     if constexpr (SPLIT) {
         // fp32 partial sums of this chunk (dK unscaled); the reduction kernel adds the chunks in a fixed order
-        const size_t n_out = (size_t)gridDim.z * S * p.Hkv * D;
+        const size_t n_out = (size_t)gridDim.z * Skv * p.Hkv * D;
         float* pk = p.part + (size_t)split * n_out;
         float* pv = pk + (size_t)nsplit * n_out;
 #pragma unroll
@@ -493,8 +494,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
-                    if (krow < S) {
-                        const size_t off = (((size_t)b * S + krow) * p.Hkv + g) * D + 32 * db + lo;
+                    if (krow < Skv) {
+                        const size_t off = (((size_t)b * Skv + krow) * p.Hkv + g) * D + 32 * db + lo;
                         pk[off] = dkacc[kbk][db][r];
                         pv[off] = dvacc[kbk][db][r];
                     }
@@ -507,8 +508,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int krow = wkey0 + 32 * kbk + 8 * (r / 4) + 4 * hi + (r % 4);
-                    if (krow < S) {
-                        const size_t off = ((size_t)b * S * p.Hkv + g) * D + p.kvmap.off(krow) + 32 * db + lo;
+                    if (krow < Skv) {
+                        const size_t off = ((size_t)b * Skv * p.Hkv + g) * D + p.kvmap.off(krow) + 32 * db + lo;
                         p.dk[off] = (__bf16)(dkacc[kbk][db][r] * p.scale);
                         p.dv[off] = (__bf16)dvacc[kbk][db][r];
                     }
@@ -543,9 +544,9 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     DkdvParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
     p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
-    p.S = a.S; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
-    p.n_ktiles = (a.S + BNK - 1) / BNK;
+    p.n_ktiles = (a.Skv + BNK - 1) / BNK;
     p.nsplit = a.dkdv_splits; p.part = a.dkdv_part;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
     if (p.nsplit < 1 || (p.nsplit > 1 && !p.part)) return SP_ERR_WORKSPACE;
@@ -554,10 +555,10 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN, false>), grid, dim3(kThreads), 0, st, p);
     if (launch_status() != SP_OK) return SP_ERR_LAUNCH;
     if (p.nsplit > 1) {
-        const int64_t n_out = (int64_t)a.B * a.S * a.Hkv * D;
+        const int64_t n_out = (int64_t)a.B * a.Skv * a.Hkv * D;
         const int64_t blocks = (n_out / 4 + 255) / 256;
         hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p.part, p.dk, p.dv, n_out,
-                           p.nsplit, p.scale, a.kvmap, a.S, a.Hkv * D);
+                           p.nsplit, p.scale, a.kvmap, a.Skv, a.Hkv * D);
     }
     return launch_status();
 }

@@ -5,6 +5,10 @@
 //   dQ_i = scale * sum_{j<=i} dS_ij k_j,   dS_ij = P_ij (dO_i.v_j - Delta_i),
 //   P_ij = exp(scale * q_i.k_j - LSE_i)
 //
+// As in the forward kernel, the general problem is S query rows against Skv
+// keys with row i seeing keys j <= i + off (one step of a ring schedule,
+// Section 4.1); the plain causal call is Skv = S, off = 0.
+//
 // One workgroup = 4 waves = 256 query rows of one query head, one wave per SIMD;
 // a wave owns 64 rows (two 32-row blocks): their Q and dO stay resident as MFMA
 // B operands (in accumulation registers), their dQ lives in accumulation
@@ -49,7 +53,7 @@ struct DqParams {
     __bf16* dq;
     const int32_t* row_lo;
     RowMap qmap, kvmap;
-    int32_t S, Hq, Hkv, G, n_qtiles;
+    int32_t S, Skv, off, Hq, Hkv, G, n_qtiles;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale, scale_log2;
 };
 
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const int h = blockIdx.x % p.Hq;
     const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
     const int b = blockIdx.y, g = h / p.G;
-    const int S = p.S;
+    const int S = p.S, Skv = p.Skv;
     const __bf16* qb_ = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + h) * D;
 
@@ -122,9 +126,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
         for (int db = 0; db < NDB; ++db)
             tb[half][db] = sm + tile_off_tr<D>(8 * half + 4 * hi, 32 * db + 16 * (lo >> 4), lo & 15);
 
+    // the last key a row may see: i + off, at most the last key there is
+    auto last_key = [&](int row) __attribute__((always_inline)) { return row + p.off < Skv - 1 ? row + p.off : Skv - 1; };
     const int jt_begin = VARLEN ? wg_lo_min / BN : 0;
     const int last_row = (i0 + BM - 1 < S ? i0 + BM - 1 : S - 1);
-    const int jt_end = last_row / BN + 1;  // exclusive
+    const int jt_end = last_key(last_row) / BN + 1;  // exclusive
     const int total = jt_end - jt_begin;   // steps = key tiles, ascending
 
     // ---- global -> LDS loads of a step: K rows (PW), V rows (PW) per wave ----
@@ -143,13 +149,13 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     uint32_t voff[PW];  // offsets of the tile the load cursor is on
 #pragma unroll
     for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, BN - 1);
-    const int jt_tail = (S % BN != 0) ? (S - 1) / BN : -1;  // the tile that runs past the last row, if any
+    const int jt_tail = (Skv % BN != 0) ? (Skv - 1) / BN : -1;  // the tile that runs past the last row, if any
     const int tiles_per_chunk_mask = (int)(p.kvmap.mask / BN);  // tiles per peer chunk - 1 (chunks are powers of two)
 
     // the step being loaded: scalar byte pointers to its tile in k and v
     struct LoadCursor { const char* k; const char* v; int jt, left; };
     LoadCursor dc;
-    const size_t head0 = ((size_t)b * S * p.Hkv + g) * D * 2;
+    const size_t head0 = ((size_t)b * Skv * p.Hkv + g) * D * 2;
     const char* const k_head = reinterpret_cast<const char*>(p.k) + head0;
     const char* const v_head = reinterpret_cast<const char*>(p.v) + head0;
     const size_t tile_step_b = (size_t)BN * stride_b;
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     auto enter_tile = [&]() __attribute__((always_inline)) {
         if (dc.jt == jt_tail) {  // rare
 #pragma unroll
-            for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, S - 1 - dc.jt * BN);
+            for (int K = 0; K < PW; ++K) voff[K] = lane_off(K, Skv - 1 - dc.jt * BN);
         }
     };
     {
@@ -190,9 +196,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     // ---- prologue: the first LEAD steps' tiles, and a finite stand-in for the deferred dQ of "step -1" ----
     int cur_jt = jt_begin;  // key tile of the step being computed
     int step_no = 0;        // its number (the step count is padded to a multiple of NBUF: steps >= total are not real)
-    // steps whose S' needs masking: from the first whose keys reach past the wave's first row (and every
-    // padding step), and, for packed documents, those before the wave's last row's document starts
-    const int mask_from = (wrow0 / BN - jt_begin) < total ? (wrow0 / BN - jt_begin) : total;
+    // steps whose S' needs masking: from the first whose keys reach past the last key the wave's first row
+    // may see (and every padding step), and, for packed documents, those before the wave's last row's
+    // document starts
+    const int mask_from = (last_key(wrow0) / BN - jt_begin) < total ? (last_key(wrow0) / BN - jt_begin) : total;
     const int mask_until = VARLEN ? (wave_lo_max + BN - 1) / BN - jt_begin : 0;
     {
         static_for<0, PW>([&](auto K) { issue_load(K, NBUF - 1); });  // K rows of step 0 again, as the stand-in
@@ -334,10 +341,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
                         for (int qb = 0; qb < 2; ++qb) {
                             const int row = wrow0 + 32 * qb + (int)(__lane_id() & 31);
                             const int rlo = VARLEN ? p.row_lo[row < S ? row : S - 1] : 0;  // first key the row may see
+                            const int rhi = row + p.off < p.Skv - 1 ? row + p.off : p.Skv - 1;  // and the last
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int key = j0 + 8 * (r / 4) + 4 * (int)(__lane_id() >> 5) + (r % 4);
-                                const bool vis = real && key <= row && key >= rlo;
+                                const bool vis = real && key <= rhi && key >= rlo;
                                 sacc[qb][r] = vis ? sacc[qb][r] : -__builtin_inff();
                             }
                         }
@@ -417,7 +425,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     DqParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
     p.lse = a.lse; p.delta = a.delta; p.dq = (__bf16*)a.dq; p.row_lo = a.row_lo;
-    p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;

@@ -1,6 +1,9 @@
 // Causal grouped-query attention, forward, for one device's head shard over
 // the full sequence (paper Section 2: every device computes attention locally
 // on its heads over the whole context; Section 3.1 challenge 3: causal mask).
+// The same kernel serves one step of a ring schedule (Section 4.1: keys and
+// values arrive block by block): S query rows against Skv keys, row i seeing
+// keys j <= i + off; the plain causal call is Skv = S, off = 0.
 //
 // One workgroup = 8 waves = 256 query rows of one query head; a wave owns 32
 // rows.  Keys/values stream through LDS in tiles of 64, double-buffered and
@@ -37,7 +40,7 @@ struct FwdParams {
     __bf16* o; float* lse;
     const int32_t* row_lo;
     RowMap qmap, kvmap;
-    int32_t S, Hq, Hkv, G, n_qtiles;
+    int32_t S, Skv, off, Hq, Hkv, G, n_qtiles;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale_log2;  // softmax_scale * log2(e)
 };
 
@@ -61,10 +64,10 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     const int h = blockIdx.x % p.Hq;
     const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
     const int b = blockIdx.y, g = h / p.G;
-    const int S = p.S;
+    const int S = p.S, Skv = p.Skv;
     const __bf16* qb = p.q + ((size_t)b * S * p.Hq + h) * D;
-    const __bf16* kb = p.k + ((size_t)b * S * p.Hkv + g) * D;
-    const __bf16* vb = p.v + ((size_t)b * S * p.Hkv + g) * D;
+    const __bf16* kb = p.k + ((size_t)b * Skv * p.Hkv + g) * D;
+    const __bf16* vb = p.v + ((size_t)b * Skv * p.Hkv + g) * D;
 
     const int i0 = qt * BM;
     const int wrow0 = i0 + 32 * wave;            // first row of this wave
@@ -84,11 +87,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
         wave_lo_max = __builtin_amdgcn_readfirstlane(p.row_lo[(wrow0 + 31 < S ? wrow0 + 31 : S - 1)]);
         wg_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[i0]);
     }
-    const int wave_q_min = wrow0, wave_q_max = wrow0 + 31;
+    // the last key a row may see: i + off, at most the last key there is
+    auto last_key = [&](int row) __attribute__((always_inline)) { return row + p.off < Skv - 1 ? row + p.off : Skv - 1; };
+    const int qhi = last_key(qrow);
+    const int wave_hi_min = last_key(wrow0), wave_hi_max = last_key(wrow0 + 31);
 
     const int jt_begin = VARLEN ? wg_lo_min / BN : 0;
     const int last_row = (i0 + BM - 1 < S ? i0 + BM - 1 : S - 1);
-    const int T = last_row / BN + 1 - jt_begin;  // tiles this workgroup walks (>= 1)
+    const int T = last_key(last_row) / BN + 1 - jt_begin;  // tiles this workgroup walks (>= 1)
 
     // LDS byte offsets of this lane's operand reads, tile-invariant
     int koff[D / 16];  // K row-major operand: row 32*nb + lo (nb adds a constant), chunk 2*kk + hi
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     // does this wave have any visible key in tile j (relative index)?
     auto tile_active = [&](int j) __attribute__((always_inline)) {
         const int j0 = (jt_begin + j) * BN;
-        bool active = j0 <= wave_q_max;
+        bool active = j0 <= wave_hi_max;
         if (VARLEN) active = active && (j0 + BN > wave_lo_min);
         return active;
     };
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     auto softmax_phase = [&](int j) __attribute__((always_inline)) {
         if (j < 0 || j >= T || !tile_active(j)) return;
         const int j0 = (jt_begin + j) * BN;
-        bool need_mask = j0 + BN - 1 > wave_q_min;
+        bool need_mask = j0 + BN - 1 > wave_hi_min;
         if (VARLEN) need_mask = need_mask || (j0 < wave_lo_max);
         if (need_mask) {
 #pragma unroll
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = j0 + 32 * nb + 8 * (r / 4) + 4 * hi + (r % 4);
-                    bool vis = key <= qrow;
+                    bool vis = key <= qhi;
                     if (VARLEN) vis = vis && key >= row_lo;
                     if (!vis) sacc[nb][r] = -INFINITY;
                 }
@@ -256,8 +262,8 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
 
     // pair j = (K tile j, V tile j-1) -> the given buffers
     auto issue_pair = [&](__bf16* kbuf, __bf16* vbuf, int j) __attribute__((always_inline)) {
-        if (j < T) dma.issue(kb + p.kvmap.off((jt_begin + j) * BN), S - 1 - (jt_begin + j) * BN, kbuf, wave);
-        if (j >= 1 && j <= T) dma.issue(vb + p.kvmap.off((jt_begin + j - 1) * BN), S - 1 - (jt_begin + j - 1) * BN, vbuf, wave);
+        if (j < T) dma.issue(kb + p.kvmap.off((jt_begin + j) * BN), Skv - 1 - (jt_begin + j) * BN, kbuf, wave);
+        if (j >= 1 && j <= T) dma.issue(vb + p.kvmap.off((jt_begin + j - 1) * BN), Skv - 1 - (jt_begin + j - 1) * BN, vbuf, wave);
     };
 
     issue_pair(ks0, vs0, 0);
@@ -316,7 +322,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     FwdParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v;
     p.o = (__bf16*)a.o; p.lse = a.lse; p.row_lo = a.row_lo;
-    p.S = a.S; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale_log2 = a.scale * kLog2e;

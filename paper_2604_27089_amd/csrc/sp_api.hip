@@ -97,7 +97,7 @@ size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_
     size_t n = delta_bytes(T, Hq) + 2 * aux_bytes(n_docs > 0 ? 1 : B, S_or_T, Hq);
     if (n_docs > 0) n += 2 * bounds_bytes(T);
     const int64_t Bk = n_docs > 0 ? 1 : B;
-    n += align_up(sp::dkdv_part_bytes(Bk, S_or_T, Hkv, D, sp::dkdv_split_count(Bk, S_or_T, Hq, Hkv)), 256);
+    n += align_up(sp::dkdv_part_bytes(Bk, S_or_T, Hkv, D, sp::dkdv_split_count(Bk, S_or_T, S_or_T, Hq, Hkv)), 256);
     return n < 256 ? 256 : n;
 }
 
@@ -122,6 +122,7 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
@@ -143,6 +144,7 @@ sp_status sp_attn_fwd_seqlayout(const void* q, const void* k, const void* v, voi
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.B = (int32_t)B; a.S = (int32_t)(S_l * P); a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
     a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
     a.scale = resolve_scale(softmax_scale, D);
@@ -177,10 +179,11 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
     a.S_pad = sp::aux_pitch(S);
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = stages;
-    a.dkdv_splits = sp::dkdv_split_count(B, S, Hq, Hkv);
+    a.dkdv_splits = sp::dkdv_split_count(B, S, S, Hq, Hkv);
     a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
     return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
 }
@@ -208,11 +211,12 @@ sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, con
     a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
     a.S_pad = sp::aux_pitch(S);
     a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
     a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
-    a.dkdv_splits = sp::dkdv_split_count(B, S, Hq, Hkv);
+    a.dkdv_splits = sp::dkdv_split_count(B, S, S, Hq, Hkv);
     a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
     return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
 }
@@ -241,6 +245,7 @@ sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* 
     sp::AttnArgs a{};
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse; a.row_lo = row_lo; a.row_hi = row_hi;
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     return sp::launch_attn_fwd(a, s);
@@ -276,12 +281,99 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
     a.aux = aux; a.S_pad = sp::aux_pitch(T);
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = a.S; a.off = 0;
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
-    a.dkdv_splits = sp::dkdv_split_count(1, T, Hq, Hkv);
+    a.dkdv_splits = sp::dkdv_split_count(1, T, T, Hq, Hkv);
     a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)row_hi + bounds_bytes(T)) : nullptr;
     return sp::launch_attn_bwd(a, s);
+}
+
+// ------------------------------------------------------------------ blockwise step of a ring schedule
+namespace {
+// 0 <= off, every key seen by some row; returns the offset clamped to "hides nothing"
+sp_status check_block(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D, int64_t* off) {
+    sp_status st = check_attn_shape(B, Sq, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    st = check_attn_shape(B, Skv, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (*off < 0) return SP_ERR_SHAPE;
+    if (*off > Skv) *off = Skv;
+    if (Sq > 0 && Skv > Sq + *off) return SP_ERR_SHAPE;
+    return SP_OK;
+}
+}  // namespace
+
+sp_status sp_attn_block_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
+                            int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D,
+                            int64_t causal_offset, float softmax_scale, void* hip_stream) {
+    sp_status st = check_block(B, Sq, Skv, Hq, Hkv, D, &causal_offset);
+    if (st != SP_OK) return st;
+    if (B == 0 || Sq == 0 || Hq == 0) return SP_OK;
+    if (Skv == 0) return SP_ERR_SHAPE;  // rows that see no key have no softmax
+    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
+    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
+        !sp::aligned16(lse))
+        return SP_ERR_ALIGN;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = (int32_t)Skv; a.off = (int32_t)causal_offset;
+    attention_side_maps(a);
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+}
+
+size_t sp_attn_block_bwd_workspace_bytes(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (B <= 0 || Sq <= 0 || Skv <= 0 || Hq <= 0) return 0;
+    if (check_attn_shape(B, Sq, Hq, Hkv, D) != SP_OK || check_attn_shape(B, Skv, Hq, Hkv, D) != SP_OK) return 0;
+    size_t n = delta_bytes(B * Sq, Hq) + 2 * aux_bytes(B, Sq, Hq);
+    n += align_up(sp::dkdv_part_bytes(B, Skv, Hkv, D, sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv)), 256);
+    return n < 256 ? 256 : n;
+}
+
+sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                            const void* dO, void* dq, void* dk, void* dv, void* workspace,
+                            size_t workspace_bytes, int64_t B, int64_t Sq, int64_t Skv, int32_t Hq,
+                            int32_t Hkv, int32_t D, int64_t causal_offset, float softmax_scale,
+                            int32_t stages, void* hip_stream) {
+    sp_status st = check_block(B, Sq, Skv, Hq, Hkv, D, &causal_offset);
+    if (st != SP_OK) return st;
+    if (stages <= 0 || (stages & ~SP_BWD_STAGE_ALL) != 0) return SP_ERR_SHAPE;
+    if (B == 0 || Sq == 0 || Hq == 0) return SP_OK;
+    if (Skv == 0) return SP_ERR_SHAPE;
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D)) return SP_ERR_WORKSPACE;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
+    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
+    a.aux = (float*)((char*)workspace + delta_bytes(B * Sq, Hq));
+    a.S_pad = sp::aux_pitch(Sq);
+    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = (int32_t)Skv; a.off = (int32_t)causal_offset;
+    attention_side_maps(a);
+    a.scale = resolve_scale(softmax_scale, D);
+    a.stages = stages;
+    a.dkdv_splits = sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv);
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, Sq, Hq)) : nullptr;
+    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, const float* lse_blk, void* o_out,
+                        int64_t B, int64_t S, int32_t Hq, int32_t D, void* hip_stream) {
+    if (B < 0 || S < 0 || Hq < 0) return SP_ERR_SHAPE;
+    if (D != 64 && D != 128) return SP_ERR_UNSUPPORTED;
+    if (B * S >= (int64_t)1 << 31 || (Hq > 0 && B * S * Hq >= (int64_t)1 << 40)) return SP_ERR_SHAPE;
+    if (B == 0 || S == 0 || Hq == 0) return SP_OK;
+    if (!o_acc || !lse_acc || !o_blk || !lse_blk) return SP_ERR_NULL;
+    if (!sp::aligned16(o_acc) || !sp::aligned16(lse_acc) || !sp::aligned16(o_blk) || !sp::aligned16(lse_blk) ||
+        !sp::aligned16(o_out))
+        return SP_ERR_ALIGN;
+    return sp::launch_attn_merge(o_acc, lse_acc, o_blk, lse_blk, o_out, B, S, Hq, D, (hipStream_t)hip_stream);
 }
 
 // ------------------------------------------------------------------ pointwise operators outside attention

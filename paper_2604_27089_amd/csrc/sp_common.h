@@ -38,7 +38,10 @@ struct RowMap {
 
 // One attention problem as the kernels see it.  Dense calls are B independent
 // sequences of S rows; packed-document calls are B = 1, S = T rows with a
-// per-row visibility window taken from `row_lo` / `row_hi`.
+// per-row visibility window taken from `row_lo` / `row_hi`.  In general the S
+// query rows face Skv keys and row i sees keys j <= i + off (one step of a ring
+// schedule); every key must be seen by some row (Skv <= S + off, off >= 0).
+// Causal attention over one sequence is Skv = S, off = 0.
 struct AttnArgs {
     const void* q; const void* k; const void* v;   // bf16
     void* o; float* lse;                           // fwd outputs (bwd: inputs)
@@ -50,6 +53,7 @@ struct AttnArgs {
     const int32_t* row_lo;  // varlen: first row of the row's document, [S]; null if dense
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
     int32_t B, S, Hq, Hkv, D;
+    int32_t Skv, off;       // keys per sequence; causal offset
     RowMap qmap, kvmap;     // layout of q, o, dO, dq and of k, v, dk, dv
     float scale;            // softmax scale (already defaulted)
     int32_t stages;         // bwd: bit mask of SP_BWD_STAGE_*
@@ -65,6 +69,8 @@ sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dq(const AttnArgs& a, hipStream_t st);
+sp_status launch_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, const float* lse_blk, void* o_out,
+                            int64_t B, int64_t S, int32_t Hq, int32_t D, hipStream_t st);
 
 // How many workgroups share one 256-key tile of the dK/dV kernel.  A key tile's work is every row from
 // its diagonal to the end of the sequence (or document), for every query head of the group: with one KV
@@ -74,17 +80,17 @@ sp_status launch_attn_bwd_dq(const AttnArgs& a, hipStream_t st);
 // each, whose fp32 partial sums a second kernel adds in a fixed order.  About 2048 workgroups, at most 8
 // chunks (measured: 4.36 -> 1.65 ms at 32K rows, 10.1 -> 6.3 ms at 64K, 25.3 -> 24.7 ms at 128K).  The
 // count depends on the extents only, so packed documents and dense calls of equal extents agree bitwise.
-inline int32_t dkdv_split_count(int64_t B, int64_t S, int32_t Hq, int32_t Hkv) {
-    if (B <= 0 || S <= 0 || Hkv <= 0) return 1;
-    const int64_t tiles = (S + 255) / 256 * Hkv * B;
+inline int32_t dkdv_split_count(int64_t B, int64_t S, int64_t Skv, int32_t Hq, int32_t Hkv) {
+    if (B <= 0 || S <= 0 || Skv <= 0 || Hkv <= 0) return 1;
+    const int64_t tiles = (Skv + 255) / 256 * Hkv * B;
     int64_t n = (2048 + tiles - 1) / tiles;
     const int64_t steps_first = (S + 31) / 32 * (Hq / Hkv);  // steps of the longest key tile
     if (n > steps_first / 32) n = steps_first / 32;            // chunks of at least 32 steps
     if (n > 8) n = 8;
     return n < 1 ? 1 : (int32_t)n;
 }
-inline size_t dkdv_part_bytes(int64_t B, int64_t S, int32_t Hkv, int32_t D, int32_t nsplit) {
-    return nsplit > 1 ? (size_t)2 * nsplit * B * S * Hkv * D * sizeof(float) : 0;
+inline size_t dkdv_part_bytes(int64_t B, int64_t Skv, int32_t Hkv, int32_t D, int32_t nsplit) {
+    return nsplit > 1 ? (size_t)2 * nsplit * B * Skv * Hkv * D * sizeof(float) : 0;
 }
 
 // pointwise operators outside attention (pointwise.hip)

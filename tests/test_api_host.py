@@ -92,6 +92,34 @@ def test_attention_argument_errors():
     assert sb(*args, need8, 1, 500, 4, 1, 128, 8, 0.0, None) == sp.SP_ERR_UNSUPPORTED
 
 
+def test_block_step_argument_errors():
+    L = sp.lib()
+    bf = L.sp_attn_block_fwd
+    five = [A(i) for i in range(1, 6)]
+    assert bf(*five, 1, 256, 256, 4, 1, 128, -1, 0.0, None) == sp.SP_ERR_SHAPE       # negative offset
+    assert bf(*five, 1, 256, 512, 4, 1, 128, 100, 0.0, None) == sp.SP_ERR_SHAPE      # keys no row sees
+    assert bf(*five, 1, 256, 512, 4, 3, 128, 511, 0.0, None) == sp.SP_ERR_SHAPE      # Hq % Hkv
+    assert bf(*five, 1, 256, 512, 4, 1, 96, 511, 0.0, None) == sp.SP_ERR_UNSUPPORTED
+    assert bf(*five, 1, 256, 0, 4, 1, 128, 0, 0.0, None) == sp.SP_ERR_SHAPE          # no keys at all
+    assert bf(None, *five[1:], 1, 256, 512, 4, 1, 128, 511, 0.0, None) == sp.SP_ERR_NULL
+    assert bf(None, None, None, None, None, 1, 0, 512, 4, 1, 128, 1 << 40, 0.0, None) == sp.SP_OK  # no rows
+    need = sp.sp_attn_block_bwd_workspace_bytes(1, 1024, 2048, 4, 1, 128)
+    assert need >= 4 * 1024 * 4
+    assert sp.sp_attn_block_bwd_workspace_bytes(1, 1024, 2048, 4, 3, 128) == 0
+    bb = L.sp_attn_block_bwd
+    args = [A(i) for i in range(1, 11)]
+    assert bb(*args, need - 1, 1, 1024, 2048, 4, 1, 128, 2048, 0.0, 7, None) == sp.SP_ERR_WORKSPACE
+    assert bb(*args, need, 1, 1024, 2048, 4, 1, 128, 2048, 0.0, 0, None) == sp.SP_ERR_SHAPE  # no stage
+    assert bb(*args, need, 1, 1024, 2048, 4, 1, 128, 512, 0.0, 7, None) == sp.SP_ERR_SHAPE
+    assert bb(*args[:9], None, need, 1, 1024, 2048, 4, 1, 128, 2048, 0.0, 7, None) == sp.SP_ERR_NULL
+    mg = L.sp_attn_merge
+    assert mg(A(1), A(2), A(3), A(4), None, 1, 256, 4, 96, None) == sp.SP_ERR_UNSUPPORTED
+    assert mg(A(1), A(2), A(3), A(4), None, 1, -1, 4, 128, None) == sp.SP_ERR_SHAPE
+    assert mg(A(1), None, A(3), A(4), None, 1, 256, 4, 128, None) == sp.SP_ERR_NULL
+    assert mg(A(1), A(2), A(3), A(4), ctypes.c_void_p(0x4004), 1, 256, 4, 128, None) == sp.SP_ERR_ALIGN
+    assert mg(None, None, None, None, None, 1, 0, 4, 128, None) == sp.SP_OK
+
+
 def test_pointwise_argument_errors():
     L = sp.lib()
     assert L.sp_rmsnorm_fwd(A(1), A(2), A(3), A(4), 4, 4100, 1e-5, None) == sp.SP_ERR_UNSUPPORTED   # C % 8
