@@ -321,6 +321,32 @@ def main():
             t = time_fn(folded, max(3, args.steps // 2), 1)
             detail["seqlayout_step"] = {"ms": t, "fwd_bwd_tflops": (fl_fwd + fl_bwd) / (t * 1e-3) / 1e12}
 
+        # One step of a ring schedule for the same model and sequence (Section 4.1: the scheme the paper
+        # compares against): the sequence stays sharded, so a device holds a block of S/P rows of every head and
+        # per arriving key/value block computes a block forward + merge, resp. the block pair's gradient shares.
+        if not args.no_other_shards:
+            n_r, hq_r, hkv_r = S // P, Hq * P, Hkv * P
+            rq_, rdo_ = (torch.empty((1, n_r, hq_r, D), **bf).normal_() for _ in range(2))
+            rk_, rv_ = (torch.empty((1, n_r, hkv_r, D), **bf).normal_() for _ in range(2))
+            ro_, rlse_ = sp.sp_attn_block_fwd(rq_, rk_, rv_, 0)
+            racc = torch.zeros((1, n_r, hq_r, D), dtype=torch.float32, device=dev)
+            rlacc = torch.zeros((1, hq_r, n_r), dtype=torch.float32, device=dev)
+            rws = torch.empty(sp.sp_attn_block_bwd_workspace_bytes(1, n_r, n_r, hq_r, hkv_r, D), dtype=torch.uint8, device=dev)
+            rdq, rdk, rdv = torch.empty_like(rq_), torch.empty_like(rk_), torch.empty_like(rv_)
+            ring = {"shard": f"block of {n_r} rows, {hq_r}q/{hkv_r}kv D={D}"}
+            for kind, off_r, pairs in (("past_block", n_r, float(n_r) * n_r), ("diagonal_block", 0, n_r * (n_r + 1) / 2.0)):
+                tf = time_fn(lambda: sp.sp_attn_block_fwd(rq_, rk_, rv_, off_r, o=ro_, lse=rlse_), 5, 1)
+                tb = time_fn(lambda: sp.sp_attn_block_bwd(rq_, rk_, rv_, ro_, rlse_, rdo_, off_r, dq=rdq, dk=rdk, dv=rdv,
+                                                          workspace=rws), 5, 1)
+                ring[kind] = {"fwd_ms": tf, "bwd_ms": tb,
+                              "fwd_tflops": 4.0 * D * hq_r * pairs / (tf * 1e-3) / 1e12,
+                              "bwd_tflops": 10.0 * D * hq_r * pairs / (tb * 1e-3) / 1e12}
+            tm = time_fn(lambda: sp.sp_attn_merge(racc, rlacc, ro_, rlse_), 20, 3)
+            mbytes = 10.0 * racc.numel() + 12.0 * rlacc.numel()  # O: fp32 in and out, bf16 in; LSE: two in, one out
+            ring["merge"] = {"us": tm * 1e3, "bytes": mbytes, "GBps": mbytes / tm / 1e6, "peak_GBps": HBM_PEAK_GBPS}
+            detail["ring_block_step"] = ring
+            del rq_, rdo_, rk_, rv_, ro_, rlse_, racc, rlacc, rws, rdq, rdk, rdv
+
         # pointwise operators outside attention on the 8B-shaped token shard [16384 tokens, model dim 4096,
         # 32 heads of 128, MLP width 14336]: algorithmic bytes (every operand read once, every result written
         # once) over time, against the HBM peak
