@@ -198,3 +198,34 @@ def test_block_bwd_rectangular_matches_oracle(Sq, Skv, Hq, Hkv, D, off):
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
         err = rel_l2(host_f64(got)[0], ref)
         assert err <= GRAD_REL_L2, f"{name}: rel L2 {err:.3e}"
+
+
+def test_block_step_full_size_sampled():
+    """The benchmark's ring block (the 8B model's 16384-row block of all 32/8 heads against a block from the
+    past).  Rows are independent in the forward, and with dO non-zero on a sampled row set only, rows outside it
+    contribute nothing to any gradient: the oracle produces the sampled rows of O, LSE, dQ and ALL of dK, dV
+    from those rows alone, while the kernels do the work of a dense dO."""
+    n, Hq, Hkv, D = 16384, 32, 8, 128
+    qb, kb, vb, dob = block_inputs(77, n, n, Hq, Hkv, D)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 255, 256, n - 257, n - 2, n - 1], rng.integers(0, n, 12)]))
+    do_s = np.zeros_like(dob)
+    do_s[0, rows] = dob[0, rows]
+    q, k, v, do = (dev_bf16(t) for t in (qb, kb, vb, do_s))
+    scale = 1.0 / np.sqrt(D)
+    o, lse = sp.sp_attn_block_fwd(q, k, v, n)
+    dq, dk, dv = sp.sp_attn_block_bwd(q, k, v, o, lse, do, n)
+    torch.cuda.synchronize()
+    q64, do64 = rn.widen_bf16(qb[0, rows]), rn.widen_bf16(do_s[0, rows])
+    k64, v64 = rn.widen_bf16(kb[0]), rn.widen_bf16(vb[0])
+    o_ref, lse_ref = rb.block_attn_fwd(q64, k64, v64, scale, n)
+    idx = torch.from_numpy(rows).cuda()
+    check_o(host_f64(o[0, idx]), o_ref, "full-size block fwd")
+    assert np.abs(host_f64(lse[0][:, idx]) - lse_ref).max() <= LSE_MAX_ABS
+    delta_ref = np.einsum("shd,shd->hs", o_ref, do64)
+    rq, rk, rv = rb.block_attn_bwd(q64, k64, v64, lse_ref, delta_ref, do64, scale, n)
+    e = (rel_l2(host_f64(dq[0, idx]), rq), rel_l2(host_f64(dk)[0], rk), rel_l2(host_f64(dv)[0], rv))
+    print(f"ring block {n}x{n}: {rows.size} active rows, rel-L2 dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+    assert max(e) <= GRAD_REL_L2
+    mask = torch.ones(n, dtype=torch.bool, device="cuda"); mask[idx] = False
+    assert float(dq[0, mask].float().abs().max()) == 0.0  # rows without dO get exactly zero dQ
