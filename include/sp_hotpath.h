@@ -238,7 +238,10 @@ sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const v
  *               device only; a malformed array is undefined behaviour confined
  *               to the output values (all accesses stay inside [0, T)).
  *   max_seqlen: host upper bound on the longest document (a hint; 0 = T).
- *   workspace : >= the matching *_workspace_bytes query.
+ *   workspace : >= the matching *_workspace_bytes query.  It receives the
+ *               per-row document windows and the order in which workgroups
+ *               take the 256-row tiles (longest first: with documents of
+ *               mixed lengths a tile's work does not follow from its position).
  * ------------------------------------------------------------------------- */
 sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                              const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,

@@ -52,6 +52,7 @@ struct DkdvParams {
     __bf16* dk; __bf16* dv;
     float* part;  // nsplit > 1: fp32 partial sums, [2 (dK unscaled, dV)][nsplit][B, Skv, Hkv, D]
     const int32_t* row_hi;
+    const int32_t* order;  // packed documents: key tiles in the order workgroups take them (or null)
     RowMap qmap, kvmap;
     int32_t S, Skv, off, S_pad, Hq, Hkv, G, n_ktiles, nsplit;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale, scale_log2;
@@ -82,7 +83,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // earliest key tiles (most rows to visit) first; the nsplit workgroups that share a key tile are neighbours
     const int nsplit = SPLIT ? p.nsplit : 1;
-    const int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x, split = SPLIT ? blockIdx.x % nsplit : 0;
+    int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x;
+    const int split = SPLIT ? blockIdx.x % nsplit : 0;
+    if (VARLEN && p.order) {  // longest tile first; clamped so that a bad entry cannot become a wild address
+        const int v = __builtin_amdgcn_readfirstlane(p.order[jt]);
+        jt = v < 0 ? 0 : (v < p.n_ktiles ? v : p.n_ktiles - 1);
+    }
     const int g = blockIdx.y, b = blockIdx.z;
     const int S = p.S, Skv = p.Skv;
     const __bf16* kb = p.k + ((size_t)b * Skv * p.Hkv + g) * D;
@@ -543,7 +549,8 @@ template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
     DkdvParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
-    p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi;
+    p.aux = a.aux; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv; p.row_hi = a.row_hi; p.order = a.order_k;
+    static_assert(BNK == kOrderTile, "the tile order is made for this tile size");
     p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.S_pad = a.S_pad; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_ktiles = (a.Skv + BNK - 1) / BNK;

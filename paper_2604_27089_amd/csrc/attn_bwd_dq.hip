@@ -52,6 +52,7 @@ struct DqParams {
     const float* lse; const float* delta;
     __bf16* dq;
     const int32_t* row_lo;
+    const int32_t* order;  // packed documents: query tiles in the order workgroups take them (or null)
     RowMap qmap, kvmap;
     int32_t S, Skv, off, Hq, Hkv, G, n_qtiles;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale, scale_log2;
@@ -71,7 +72,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // heads vary fastest (they share K/V tiles), query tiles from the last (longest) to the first
     const int h = blockIdx.x % p.Hq;
-    const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    if (VARLEN && p.order) {  // longest tile first; clamped so that a bad entry cannot become a wild address
+        const int v = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x / p.Hq]);
+        qt = v < 0 ? 0 : (v < p.n_qtiles ? v : p.n_qtiles - 1);
+    }
     const int b = blockIdx.y, g = h / p.G;
     const int S = p.S, Skv = p.Skv;
     const __bf16* qb_ = p.q + ((size_t)b * S * p.Hq + h) * D;
@@ -424,7 +429,8 @@ template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
     DqParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.dO = (const __bf16*)a.dO;
-    p.lse = a.lse; p.delta = a.delta; p.dq = (__bf16*)a.dq; p.row_lo = a.row_lo;
+    p.lse = a.lse; p.delta = a.delta; p.dq = (__bf16*)a.dq; p.row_lo = a.row_lo; p.order = a.order_q;
+    static_assert(BM == kOrderTile, "the tile order is made for this tile size");
     p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;

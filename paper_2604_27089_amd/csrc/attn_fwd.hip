@@ -39,6 +39,7 @@ struct FwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v;
     __bf16* o; float* lse;
     const int32_t* row_lo;
+    const int32_t* order;  // packed documents: query tiles in the order workgroups take them (or null)
     RowMap qmap, kvmap;
     int32_t S, Skv, off, Hq, Hkv, G, n_qtiles;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale_log2;  // softmax_scale * log2(e)
@@ -62,7 +63,11 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     // share a KV head walk the same K/V tiles at the same time, and query tiles go from the last
     // (longest) to the first, which keeps the CUs evenly loaded to the end.
     const int h = blockIdx.x % p.Hq;
-    const int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    if (VARLEN && p.order) {  // longest tile first; the value is clamped so that a bad entry cannot become a wild address
+        const int v = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x / p.Hq]);
+        qt = v < 0 ? 0 : (v < p.n_qtiles ? v : p.n_qtiles - 1);
+    }
     const int b = blockIdx.y, g = h / p.G;
     const int S = p.S, Skv = p.Skv;
     const __bf16* qb = p.q + ((size_t)b * S * p.Hq + h) * D;
@@ -321,7 +326,8 @@ template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
     FwdParams p;
     p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v;
-    p.o = (__bf16*)a.o; p.lse = a.lse; p.row_lo = a.row_lo;
+    p.o = (__bf16*)a.o; p.lse = a.lse; p.row_lo = a.row_lo; p.order = a.order_q;
+    static_assert(BM == kOrderTile, "the tile order is made for this tile size");
     p.S = a.S; p.Skv = a.Skv; p.off = a.off; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;

@@ -47,13 +47,30 @@ inline int32_t seq_chunk_log2(int64_t S_l) {
 
 // Workspace layout: [delta fp32 B*Hq*S] [per-row seeds fp32 2*B*Hq*S_pad: per 32-row tile, 32 x -LSE/scale
 // then 32 x -Delta] (bwd only)
-// [row_lo int32 T] [row_hi int32 T] (varlen only)
+// [row_lo int32 T] [row_hi int32 T] [tile work 2n int32, query-tile order n, key-tile order n; n = ceil(T/256)]
+// (varlen only; the order block is absent above kMaxOrderTiles tiles)
 // [dK/dV partial sums fp32 2*nsplit*B*S*Hkv*D] (bwd only, when the dK/dV kernel splits its key tiles),
 // each part rounded up to 256 bytes.
 size_t delta_bytes(int64_t T, int32_t Hq) { return align_up((size_t)T * (size_t)Hq * sizeof(float), 256); }
 size_t bounds_bytes(int64_t T) { return align_up((size_t)T * sizeof(int32_t), 256); }
+size_t order_bytes(int64_t T) {
+    const int64_t n = sp::order_tiles(T);
+    return n <= sp::kMaxOrderTiles ? align_up((size_t)4 * n * sizeof(int32_t), 256) : 0;
+}
 size_t aux_bytes(int64_t B, int64_t S, int32_t Hq) {
     return align_up((size_t)B * (size_t)Hq * (size_t)sp::aux_pitch(S) * sizeof(float), 256);
+}
+// per-row document windows and, when the batch is small enough to have an order block (at `blk`), the
+// longest-first tile orders
+sp_status make_bounds(sp::AttnArgs& a, const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t* row_lo,
+                      int32_t* row_hi, void* blk, hipStream_t s) {
+    a.row_lo = row_lo; a.row_hi = row_hi;
+    if (order_bytes(T) == 0) return sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, nullptr, nullptr, nullptr, s);
+    const int32_t n = sp::order_tiles(T);
+    int32_t* w = (int32_t*)blk;
+    a.order_q = w + 2 * n;
+    a.order_k = w + 3 * n;
+    return sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, w, w + 2 * n, w + 3 * n, s);
 }
 
 }  // namespace
@@ -73,7 +90,7 @@ const char* sp_status_str(sp_status s) {
     return "SP_ERR_?: unknown status";
 }
 
-int32_t sp_abi_version(void) { return 2; }
+int32_t sp_abi_version(void) { return 3; }
 
 sp_status sp_pack_seq_to_head(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
                               int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream) {
@@ -95,7 +112,7 @@ size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_
     const int64_t T = n_docs > 0 ? S_or_T : B * S_or_T;
     if (check_attn_shape(n_docs > 0 ? 1 : B, S_or_T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
     size_t n = delta_bytes(T, Hq) + 2 * aux_bytes(n_docs > 0 ? 1 : B, S_or_T, Hq);
-    if (n_docs > 0) n += 2 * bounds_bytes(T);
+    if (n_docs > 0) n += 2 * bounds_bytes(T) + order_bytes(T);
     const int64_t Bk = n_docs > 0 ? 1 : B;
     n += align_up(sp::dkdv_part_bytes(Bk, S_or_T, Hkv, D, sp::dkdv_split_count(Bk, S_or_T, S_or_T, Hq, Hkv)), 256);
     return n < 256 ? 256 : n;
@@ -105,7 +122,7 @@ size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, in
                                           int32_t n_docs) {
     if (n_docs < 0) return 0;
     if (check_attn_shape(1, T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
-    const size_t n = 2 * bounds_bytes(T);
+    const size_t n = 2 * bounds_bytes(T) + order_bytes(T);
     return n < 256 ? 256 : n;
 }
 
@@ -240,10 +257,10 @@ sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* 
     hipStream_t s = (hipStream_t)hip_stream;
     int32_t* row_lo = (int32_t*)workspace;
     int32_t* row_hi = (int32_t*)((char*)workspace + bounds_bytes(T));
-    st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
-    if (st != SP_OK) return st;
     sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse; a.row_lo = row_lo; a.row_hi = row_hi;
+    st = make_bounds(a, cu_seqlens, n_docs, T, row_lo, row_hi, (char*)row_hi + bounds_bytes(T), s);
+    if (st != SP_OK) return st;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.Skv = a.S; a.off = 0;
     attention_side_maps(a);
@@ -274,11 +291,11 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     float* aux = (float*)((char*)workspace + delta_bytes(T, Hq));
     int32_t* row_lo = (int32_t*)((char*)aux + 2 * aux_bytes(1, T, Hq));
     int32_t* row_hi = (int32_t*)((char*)row_lo + bounds_bytes(T));
-    st = sp::launch_doc_bounds(cu_seqlens, n_docs, (int32_t)T, row_lo, row_hi, s);
-    if (st != SP_OK) return st;
     sp::AttnArgs a{};
+    st = make_bounds(a, cu_seqlens, n_docs, T, row_lo, row_hi, (char*)row_hi + bounds_bytes(T), s);
+    if (st != SP_OK) return st;
     a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
-    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta; a.row_lo = row_lo; a.row_hi = row_hi;
+    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = delta;
     a.aux = aux; a.S_pad = sp::aux_pitch(T);
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
     a.Skv = a.S; a.off = 0;
@@ -286,7 +303,7 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
     a.dkdv_splits = sp::dkdv_split_count(1, T, T, Hq, Hkv);
-    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)row_hi + bounds_bytes(T)) : nullptr;
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)row_hi + bounds_bytes(T) + order_bytes(T)) : nullptr;
     return sp::launch_attn_bwd(a, s);
 }
 

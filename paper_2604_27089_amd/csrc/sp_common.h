@@ -52,6 +52,8 @@ struct AttnArgs {
     int32_t S_pad;                                 // rows per head in aux (S rounded up to 64, plus 64)
     const int32_t* row_lo;  // varlen: first row of the row's document, [S]; null if dense
     const int32_t* row_hi;  // varlen: one past the last row of the row's document, [S]
+    const int32_t* order_q; // varlen: query tiles (256 rows) in the order workgroups take them; null = last first
+    const int32_t* order_k; // varlen: key tiles (256 keys) likewise; null = first first
     int32_t B, S, Hq, Hkv, D;
     int32_t Skv, off;       // keys per sequence; causal offset
     RowMap qmap, kvmap;     // layout of q, o, dO, dq and of k, v, dk, dv
@@ -63,8 +65,16 @@ struct AttnArgs {
 
 sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int64_t H, int64_t D,
                           int32_t P, int32_t elem_bytes, bool to_head, hipStream_t st);
+// Longest-first tile orders for packed documents (doc_bounds.hip).  All three attention kernels use tiles
+// of kOrderTile rows resp. keys per workgroup.  Above kMaxOrderTiles tiles the quadratic ranking is not
+// worth its time and callers pass null orders.
+constexpr int32_t kOrderTile = 256;
+constexpr int32_t kMaxOrderTiles = 16384;
+inline int32_t order_tiles(int64_t T) { return (int32_t)((T + kOrderTile - 1) / kOrderTile); }
+// Per-row document windows, and (if `work` is not null) the tile orders: `work` is scratch of
+// 2*order_tiles(T) int32, `order_q`, `order_k` receive order_tiles(T) int32 each.
 sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* row_lo,
-                            int32_t* row_hi, hipStream_t st);
+                            int32_t* row_hi, int32_t* work, int32_t* order_q, int32_t* order_k, hipStream_t st);
 sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);

@@ -82,12 +82,15 @@ def test_varlen_documents_do_not_leak():
             assert torch.equal(a[keep].view(torch.int16), b[keep].view(torch.int16))
 
 
-def test_varlen_full_size_workload():
-    """T = 65536 packed documents with lognormal lengths: sampled rows for the
-    forward and dQ, sparse dO for all of dK/dV."""
+@pytest.mark.parametrize("T,seed", [(65536, 0), (90112 + 77, 5)])
+def test_varlen_full_size_workload(T, seed):
+    """T = 65536 packed documents with lognormal lengths (the benchmark's workload), and a longer, ragged batch
+    with more than 256 tiles for the kernels that order them: sampled rows for the forward and dQ, sparse dO
+    for all of dK/dV."""
     cfg = synth.CONFIGS["c5_varlen_64k"]
-    T, Hq, Hkv, D = cfg["T"], cfg["Hq"], cfg["Hkv"], cfg["D"]
-    lengths = synth.doc_lengths(0, T)
+    assert cfg["T"] == 65536
+    Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
+    lengths = synth.doc_lengths(seed, T)
     cu = synth.cu_seqlens_from_lengths(lengths)
     q, k, v, do = synth.attn_inputs(0, T, Hq, Hkv, D)
     rng = np.random.default_rng(4)
@@ -103,5 +106,5 @@ def test_varlen_full_size_workload():
     err = check_o(host_f64(o[idx]), r["O"])
     lerr = np.abs(host_f64(lse[:, idx]) - r["lse"]).max()
     e = (rel_l2(host_f64(dq[idx]), r["dQ"]), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
-    print(f"varlen 64k ({len(lengths)} docs): O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+    print(f"varlen T={T} ({len(lengths)} docs): O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
