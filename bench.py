@@ -288,8 +288,8 @@ def main():
         vws = torch.empty(sp.sp_attn_bwd_workspace_bytes(1, T, vc["Hq"], vc["Hkv"], D, len(lengths)), dtype=torch.uint8, device=dev)
         vdq, vdk, vdv = torch.empty_like(vq), torch.empty_like(vk), torch.empty_like(vv)
         vp = sum(L * (L + 1) // 2 for L in lengths)
-        tf = time_fn(lambda: sp.sp_attn_varlen_fwd(vq, vk, vv, cu, o=vo, lse=vlse, workspace=vws), 10)
-        tb = time_fn(lambda: sp.sp_attn_varlen_bwd(vq, vk, vv, vo, vlse, vdo, cu, dq=vdq, dk=vdk, dv=vdv, workspace=vws), 10)
+        tf = time_fn(lambda: sp.sp_attn_varlen_fwd(vq, vk, vv, cu, max_seqlen=max(lengths), o=vo, lse=vlse, workspace=vws), 10)
+        tb = time_fn(lambda: sp.sp_attn_varlen_bwd(vq, vk, vv, vo, vlse, vdo, cu, max_seqlen=max(lengths), dq=vdq, dk=vdk, dv=vdv, workspace=vws), 10)
         detail["varlen"] = {"T": T, "n_docs": len(lengths), "max_len": max(lengths), "fwd_ms": tf, "bwd_ms": tb,
                             "fwd_bwd_tflops": 14.0 * D * vc["Hq"] * vp / ((tf + tb) * 1e-3) / 1e12}
 

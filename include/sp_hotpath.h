@@ -237,7 +237,10 @@ sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const v
  *               Empty documents are allowed.  The contents are read on the
  *               device only; a malformed array is undefined behaviour confined
  *               to the output values (all accesses stay inside [0, T)).
- *   max_seqlen: host upper bound on the longest document (a hint; 0 = T).
+ *   max_seqlen: host upper bound on the longest document (a hint; 0 = T).  It
+ *               never changes a result beyond rounding order: the backward uses
+ *               it to decide over how many workgroups a key tile's work is
+ *               spread (short documents want fewer).
  *   workspace : >= the matching *_workspace_bytes query.  It receives the
  *               per-row document windows and the order in which workgroups
  *               take the 256-row tiles (longest first: with documents of

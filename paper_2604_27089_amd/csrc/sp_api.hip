@@ -273,7 +273,6 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
                              const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
                              int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
                              void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)max_seqlen;
     if (n_docs < 0) return SP_ERR_SHAPE;
     sp_status st = check_attn_shape(1, T, Hq, Hkv, D);
     if (st != SP_OK) return st;
@@ -302,7 +301,7 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     a.stages = SP_BWD_STAGE_ALL;
-    a.dkdv_splits = sp::dkdv_split_count(1, T, T, Hq, Hkv);
+    a.dkdv_splits = sp::dkdv_split_count(1, T, T, Hq, Hkv, max_seqlen);  // the hint only shapes the work split
     a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)row_hi + bounds_bytes(T) + order_bytes(T)) : nullptr;
     return sp::launch_attn_bwd(a, s);
 }

@@ -87,16 +87,25 @@ sp_status launch_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, con
 // head that is one workgroup per 256 keys, far too few to fill and balance 256 compute units below a
 // few hundred thousand rows (at 32K rows: 128 workgroups, the longest doing 1/64 of all the work).  The
 // (head, row tile) steps of a key tile are therefore cut into this many contiguous chunks, one workgroup
-// each, whose fp32 partial sums a second kernel adds in a fixed order.  About 2048 workgroups, at most 8
-// chunks (measured: 4.36 -> 1.65 ms at 32K rows, 10.1 -> 6.3 ms at 64K, 25.3 -> 24.7 ms at 128K).  The
-// count depends on the extents only, so packed documents and dense calls of equal extents agree bitwise.
-inline int32_t dkdv_split_count(int64_t B, int64_t S, int64_t Skv, int32_t Hq, int32_t Hkv) {
+// each, whose fp32 partial sums a second kernel adds in a fixed order (measured: 4.36 -> 1.65 ms at 32K
+// rows, 10.1 -> 6.3 ms at 64K, 25.3 -> 24.7 ms at 128K).
+// A workgroup of this kernel costs about 45 us beyond its steps (loading its keys and values, the pipeline
+// prologue, writing 256 KB of partial sums), a step about 1.5 us, and one compute unit holds one workgroup:
+// n chunks per tile cost (tiles * n / 256) * 45 us of overhead and leave a longest chunk of steps_first / n
+// steps, a fraction of which is exposed at the end.  The sum is smallest near n = sqrt(2.1 * steps_first /
+// tiles) (the constant fitted to sequences of 1K to 128K rows, dense and packed); at most 8 chunks, and no
+// more than about 2048 workgroups.  `longest` = the longest sequence in the call when the caller knows it
+// (packed documents: the max_seqlen hint), else S.  The count depends on these extents only, so packed
+// documents and dense calls of equal extents agree bitwise.
+inline int32_t dkdv_split_count(int64_t B, int64_t S, int64_t Skv, int32_t Hq, int32_t Hkv, int64_t longest = 0) {
     if (B <= 0 || S <= 0 || Skv <= 0 || Hkv <= 0) return 1;
+    if (longest <= 0 || longest > S) longest = S;
     const int64_t tiles = (Skv + 255) / 256 * Hkv * B;
-    int64_t n = (2048 + tiles - 1) / tiles;
-    const int64_t steps_first = (S + 31) / 32 * (Hq / Hkv);  // steps of the longest key tile
-    if (n > steps_first / 32) n = steps_first / 32;            // chunks of at least 32 steps
-    if (n > 8) n = 8;
+    const int64_t steps_first = (longest + 31) / 32 * (Hq / Hkv);  // steps of the longest key tile
+    int64_t n = 1;
+    while (n < 8 && (2 * n + 1) * (2 * n + 1) * tiles * 10 <= 4 * 21 * steps_first) ++n;  // n <= sqrt(2.1 x) + 0.5
+    const int64_t cap = (2048 + tiles - 1) / tiles;
+    if (n > cap) n = cap;
     return n < 1 ? 1 : (int32_t)n;
 }
 inline size_t dkdv_part_bytes(int64_t B, int64_t Skv, int32_t Hkv, int32_t D, int32_t nsplit) {
