@@ -71,13 +71,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
     const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // heads vary fastest (they share K/V tiles), query tiles from the last (longest) to the first
-    const int h = blockIdx.x % p.Hq;
-    int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq;
+    const int rank = (int)(blockIdx.y + kRankY * blockIdx.z);
+    if (rank >= p.n_qtiles) return;  // the last z-slice of a grid of more than kRankY tiles may be ragged
+    int qt = p.n_qtiles - 1 - rank;
     if (VARLEN && p.order) {  // longest tile first; clamped so that a bad entry cannot become a wild address
-        const int v = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x / p.Hq]);
+        const int v = __builtin_amdgcn_readfirstlane(p.order[rank]);
         qt = v < 0 ? 0 : (v < p.n_qtiles ? v : p.n_qtiles - 1);
     }
-    const int b = blockIdx.y, g = h / p.G;
+    const int g = h / p.G;
     const int S = p.S, Skv = p.Skv;
     const __bf16* qb_ = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* dob = p.dO + ((size_t)b * S * p.Hq + h) * D;
@@ -435,7 +437,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
-    dim3 grid(p.n_qtiles * a.Hq, a.B);
+    const dim3 grid = tile_rank_grid(a.Hq, a.B, p.n_qtiles);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, VARLEN>), grid, dim3(kThreads), 0, st, p);
     return launch_status();
 }
@@ -445,7 +447,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
 namespace sp {
 
 sp_status launch_attn_bwd_dq(const AttnArgs& a, hipStream_t st) {
-    if (a.B > 65535) return SP_ERR_SHAPE;
+    if ((int64_t)a.B * a.Hq > 0x7fffffff) return SP_ERR_SHAPE;
     const bool varlen = a.row_lo != nullptr;
     if (a.D == 128) return varlen ? launch<128, true>(a, st) : launch<128, false>(a, st);
     if (a.D == 64) return varlen ? launch<64, true>(a, st) : launch<64, false>(a, st);

@@ -59,16 +59,18 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(FwdParams p) {
     const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = wave >> 2;  // waves w and w+4 share a SIMD and work in opposite phases
-    // Workgroups are dispatched in blockIdx.x order: heads vary fastest, so the query heads that
+    // Workgroups are dispatched in blockIdx.x order first: heads vary fastest, so the query heads that
     // share a KV head walk the same K/V tiles at the same time, and query tiles go from the last
     // (longest) to the first, which keeps the CUs evenly loaded to the end.
-    const int h = blockIdx.x % p.Hq;
-    int qt = p.n_qtiles - 1 - (int)(blockIdx.x / p.Hq);
+    const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq;
+    const int rank = (int)(blockIdx.y + kRankY * blockIdx.z);
+    if (rank >= p.n_qtiles) return;  // the last z-slice of a grid of more than kRankY tiles may be ragged
+    int qt = p.n_qtiles - 1 - rank;
     if (VARLEN && p.order) {  // longest tile first; the value is clamped so that a bad entry cannot become a wild address
-        const int v = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x / p.Hq]);
+        const int v = __builtin_amdgcn_readfirstlane(p.order[rank]);
         qt = v < 0 ? 0 : (v < p.n_qtiles ? v : p.n_qtiles - 1);
     }
-    const int b = blockIdx.y, g = h / p.G;
+    const int g = h / p.G;
     const int S = p.S, Skv = p.Skv;
     const __bf16* qb = p.q + ((size_t)b * S * p.Hq + h) * D;
     const __bf16* kb = p.k + ((size_t)b * Skv * p.Hkv + g) * D;
@@ -332,7 +334,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.qmap = a.qmap; p.kvmap = a.kvmap;
     p.n_qtiles = (a.S + BM - 1) / BM;
     p.scale_log2 = a.scale * kLog2e;
-    dim3 grid(p.n_qtiles * a.Hq, a.B), block(kThreads);
+    const dim3 grid = tile_rank_grid(a.Hq, a.B, p.n_qtiles), block(kThreads);
     hipLaunchKernelGGL((attn_fwd_kernel<D, VARLEN>), grid, block, 0, st, p);
     return launch_status();
 }
@@ -342,7 +344,7 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
 namespace sp {
 
 sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st) {
-    if (a.B > 65535) return SP_ERR_SHAPE;
+    if ((int64_t)a.B * a.Hq > 0x7fffffff) return SP_ERR_SHAPE;
     const bool varlen = a.row_lo != nullptr;
     if (a.D == 128) return varlen ? launch<128, true>(a, st) : launch<128, false>(a, st);
     if (a.D == 64) return varlen ? launch<64, true>(a, st) : launch<64, false>(a, st);

@@ -75,6 +75,15 @@ inline int32_t order_tiles(int64_t T) { return (int32_t)((T + kOrderTile - 1) / 
 // 2*order_tiles(T) int32, `order_q`, `order_k` receive order_tiles(T) int32 each.
 sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* row_lo,
                             int32_t* row_hi, int32_t* work, int32_t* order_q, int32_t* order_k, hipStream_t st);
+// Grid of the forward and dQ kernels: x = head + Hq * batch, (y, z) = rank of the query tile in the order the
+// tiles are taken (rank = y + kRankY * z).  Workgroups are dispatched x first, so all heads and batch entries
+// of the longest tile go out before any shorter tile (a batch-major order would end with the long tiles of
+// the last batch entry).
+constexpr uint32_t kRankY = 32768;
+inline dim3 tile_rank_grid(int32_t Hq, int32_t B, int32_t n_tiles) {
+    return dim3((uint32_t)Hq * (uint32_t)B, (uint32_t)n_tiles < kRankY ? (uint32_t)n_tiles : kRankY,
+                ((uint32_t)n_tiles + kRankY - 1) / kRankY);
+}
 sp_status launch_attn_fwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd(const AttnArgs& a, hipStream_t st);
 sp_status launch_attn_bwd_dkdv(const AttnArgs& a, hipStream_t st);
