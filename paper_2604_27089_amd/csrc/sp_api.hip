@@ -60,6 +60,42 @@ size_t order_bytes(int64_t T) {
 size_t aux_bytes(int64_t B, int64_t S, int32_t Hq) {
     return align_up((size_t)B * (size_t)Hq * (size_t)sp::aux_pitch(S) * sizeof(float), 256);
 }
+// The dense backward entry points differ in extents, causal offset and row maps only; this is their common
+// tail: pointer checks, carving the workspace ([delta][per-row seeds][dK/dV partial sums]), launch.
+struct BwdBuffers {
+    const void* q; const void* k; const void* v; const void* o; const float* lse; const void* dO;
+    void* dq; void* dk; void* dv; void* workspace; size_t workspace_bytes;
+};
+size_t dense_bwd_bytes(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D) {
+    size_t n = delta_bytes(B * Sq, Hq) + 2 * aux_bytes(B, Sq, Hq);
+    n += align_up(sp::dkdv_part_bytes(B, Skv, Hkv, D, sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv)), 256);
+    return n < 256 ? 256 : n;
+}
+sp_status run_dense_bwd(const BwdBuffers& t, int64_t B, int64_t Sq, int64_t Skv, int64_t off, int32_t Hq,
+                        int32_t Hkv, int32_t D, const sp::RowMap& qmap, const sp::RowMap& kvmap,
+                        float softmax_scale, int32_t stages, void* hip_stream) {
+    if (stages <= 0 || (stages & ~SP_BWD_STAGE_ALL) != 0) return SP_ERR_SHAPE;
+    if (!t.q || !t.k || !t.v || !t.o || !t.lse || !t.dO || !t.dq || !t.dk || !t.dv || !t.workspace) return SP_ERR_NULL;
+    const void* ptrs[] = {t.q, t.k, t.v, t.o, t.lse, t.dO, t.dq, t.dk, t.dv, t.workspace};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if (t.workspace_bytes < dense_bwd_bytes(B, Sq, Skv, Hq, Hkv, D)) return SP_ERR_WORKSPACE;
+    sp::AttnArgs a{};
+    a.q = t.q; a.k = t.k; a.v = t.v; a.o = const_cast<void*>(t.o); a.lse = const_cast<float*>(t.lse);
+    a.dO = t.dO; a.dq = t.dq; a.dk = t.dk; a.dv = t.dv;
+    a.delta = (float*)t.workspace;
+    a.aux = (float*)((char*)t.workspace + delta_bytes(B * Sq, Hq));
+    a.S_pad = sp::aux_pitch(Sq);
+    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = (int32_t)Skv; a.off = (int32_t)off;
+    a.qmap = qmap; a.kvmap = kvmap;
+    a.scale = resolve_scale(softmax_scale, D);
+    a.stages = stages;
+    a.dkdv_splits = sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv);
+    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, Sq, Hq)) : nullptr;
+    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+}
+
 // per-row document windows and, when the batch is small enough to have an order block (at `blk`), the
 // longest-first tile orders
 sp_status make_bounds(sp::AttnArgs& a, const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t* row_lo,
@@ -109,13 +145,12 @@ sp_status sp_unpack_head_to_seq(const void* in, void* out, int64_t B, int64_t S_
 size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_t Hkv, int32_t D,
                                    int32_t n_docs) {
     if (n_docs < 0 || B <= 0) return 0;
-    const int64_t T = n_docs > 0 ? S_or_T : B * S_or_T;
     if (check_attn_shape(n_docs > 0 ? 1 : B, S_or_T, Hq, Hkv, D) != SP_OK || Hq == 0) return 0;
-    size_t n = delta_bytes(T, Hq) + 2 * aux_bytes(n_docs > 0 ? 1 : B, S_or_T, Hq);
-    if (n_docs > 0) n += 2 * bounds_bytes(T) + order_bytes(T);
-    const int64_t Bk = n_docs > 0 ? 1 : B;
-    n += align_up(sp::dkdv_part_bytes(Bk, S_or_T, Hkv, D, sp::dkdv_split_count(Bk, S_or_T, S_or_T, Hq, Hkv)), 256);
-    return n < 256 ? 256 : n;
+    if (n_docs == 0) return dense_bwd_bytes(B, S_or_T, S_or_T, Hq, Hkv, D);
+    // packed documents: one sequence of T rows, with the windows and tile orders between the seeds and the
+    // partial sums (sized for the largest work split, i.e. without a max_seqlen hint)
+    const int64_t T = S_or_T;
+    return dense_bwd_bytes(1, T, T, Hq, Hkv, D) + 2 * bounds_bytes(T) + order_bytes(T);
 }
 
 size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
@@ -185,24 +220,9 @@ sp_status sp_attn_bwd_stages(const void* q, const void* k, const void* v, const 
     if (st != SP_OK) return st;
     if (stages <= 0 || (stages & ~SP_BWD_STAGE_ALL) != 0) return SP_ERR_SHAPE;
     if (B == 0 || S == 0 || Hq == 0) return SP_OK;
-    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
-    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
-    for (const void* p : ptrs)
-        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
-    if (workspace_bytes < sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0)) return SP_ERR_WORKSPACE;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
-    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
-    a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
-    a.S_pad = sp::aux_pitch(S);
-    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = a.S; a.off = 0;
-    attention_side_maps(a);
-    a.scale = resolve_scale(softmax_scale, D);
-    a.stages = stages;
-    a.dkdv_splits = sp::dkdv_split_count(B, S, S, Hq, Hkv);
-    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
-    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+    const BwdBuffers t{q, k, v, o, lse, dO, dq, dk, dv, workspace, workspace_bytes};
+    return run_dense_bwd(t, B, S, S, 0, Hq, Hkv, D, sp::RowMap::attention_side(Hq, D),
+                         sp::RowMap::attention_side(Hkv, D), softmax_scale, stages, hip_stream);
 }
 
 sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, const void* o,
@@ -217,25 +237,9 @@ sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, con
     if (B == 0 || S == 0 || Hq == 0) return SP_OK;
     const int32_t lg = seq_chunk_log2(S_l);
     if (lg < 0) return SP_ERR_UNSUPPORTED;
-    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
-    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
-    for (const void* p : ptrs)
-        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
-    if (workspace_bytes < sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0)) return SP_ERR_WORKSPACE;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
-    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
-    a.aux = (float*)((char*)workspace + delta_bytes(B * S, Hq));
-    a.S_pad = sp::aux_pitch(S);
-    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = a.S; a.off = 0;
-    a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
-    a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
-    a.scale = resolve_scale(softmax_scale, D);
-    a.stages = SP_BWD_STAGE_ALL;
-    a.dkdv_splits = sp::dkdv_split_count(B, S, S, Hq, Hkv);
-    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, S, Hq)) : nullptr;
-    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+    const BwdBuffers t{q, k, v, o, lse, dO, dq, dk, dv, workspace, workspace_bytes};
+    return run_dense_bwd(t, B, S, S, 0, Hq, Hkv, D, sp::RowMap::sequence_side(lg, Hq, D, P),
+                         sp::RowMap::sequence_side(lg, Hkv, D, P), softmax_scale, SP_BWD_STAGE_ALL, hip_stream);
 }
 
 sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -344,9 +348,7 @@ sp_status sp_attn_block_fwd(const void* q, const void* k, const void* v, void* o
 size_t sp_attn_block_bwd_workspace_bytes(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D) {
     if (B <= 0 || Sq <= 0 || Skv <= 0 || Hq <= 0) return 0;
     if (check_attn_shape(B, Sq, Hq, Hkv, D) != SP_OK || check_attn_shape(B, Skv, Hq, Hkv, D) != SP_OK) return 0;
-    size_t n = delta_bytes(B * Sq, Hq) + 2 * aux_bytes(B, Sq, Hq);
-    n += align_up(sp::dkdv_part_bytes(B, Skv, Hkv, D, sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv)), 256);
-    return n < 256 ? 256 : n;
+    return dense_bwd_bytes(B, Sq, Skv, Hq, Hkv, D);
 }
 
 sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
@@ -359,24 +361,9 @@ sp_status sp_attn_block_bwd(const void* q, const void* k, const void* v, const v
     if (stages <= 0 || (stages & ~SP_BWD_STAGE_ALL) != 0) return SP_ERR_SHAPE;
     if (B == 0 || Sq == 0 || Hq == 0) return SP_OK;
     if (Skv == 0) return SP_ERR_SHAPE;
-    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv || !workspace) return SP_ERR_NULL;
-    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv, workspace};
-    for (const void* p : ptrs)
-        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
-    if (workspace_bytes < sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D)) return SP_ERR_WORKSPACE;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse);
-    a.dO = dO; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
-    a.aux = (float*)((char*)workspace + delta_bytes(B * Sq, Hq));
-    a.S_pad = sp::aux_pitch(Sq);
-    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = (int32_t)Skv; a.off = (int32_t)causal_offset;
-    attention_side_maps(a);
-    a.scale = resolve_scale(softmax_scale, D);
-    a.stages = stages;
-    a.dkdv_splits = sp::dkdv_split_count(B, Sq, Skv, Hq, Hkv);
-    a.dkdv_part = a.dkdv_splits > 1 ? (float*)((char*)a.aux + 2 * aux_bytes(B, Sq, Hq)) : nullptr;
-    return sp::launch_attn_bwd(a, (hipStream_t)hip_stream);
+    const BwdBuffers t{q, k, v, o, lse, dO, dq, dk, dv, workspace, workspace_bytes};
+    return run_dense_bwd(t, B, Sq, Skv, causal_offset, Hq, Hkv, D, sp::RowMap::attention_side(Hq, D),
+                         sp::RowMap::attention_side(Hkv, D), softmax_scale, stages, hip_stream);
 }
 
 sp_status sp_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, const float* lse_blk, void* o_out,
