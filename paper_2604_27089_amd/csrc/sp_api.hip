@@ -60,6 +60,23 @@ size_t order_bytes(int64_t T) {
 size_t aux_bytes(int64_t B, int64_t S, int32_t Hq) {
     return align_up((size_t)B * (size_t)Hq * (size_t)sp::aux_pitch(S) * sizeof(float), 256);
 }
+// common tail of the dense forward entry points
+sp_status run_dense_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t Sq,
+                        int64_t Skv, int64_t off, int32_t Hq, int32_t Hkv, int32_t D, const sp::RowMap& qmap,
+                        const sp::RowMap& kvmap, float softmax_scale, void* hip_stream) {
+    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
+    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
+        !sp::aligned16(lse))
+        return SP_ERR_ALIGN;
+    sp::AttnArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Skv = (int32_t)Skv; a.off = (int32_t)off;
+    a.qmap = qmap; a.kvmap = kvmap;
+    a.scale = resolve_scale(softmax_scale, D);
+    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+}
+
 // The dense backward entry points differ in extents, causal offset and row maps only; this is their common
 // tail: pointer checks, carving the workspace ([delta][per-row seeds][dK/dV partial sums]), launch.
 struct BwdBuffers {
@@ -167,17 +184,8 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
     sp_status st = check_attn_shape(B, S, Hq, Hkv, D);
     if (st != SP_OK) return st;
     if (B == 0 || S == 0 || Hq == 0) return SP_OK;
-    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
-    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
-        !sp::aligned16(lse))
-        return SP_ERR_ALIGN;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
-    a.B = (int32_t)B; a.S = (int32_t)S; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = a.S; a.off = 0;
-    attention_side_maps(a);
-    a.scale = resolve_scale(softmax_scale, D);
-    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+    return run_dense_fwd(q, k, v, o, lse, B, S, S, 0, Hq, Hkv, D, sp::RowMap::attention_side(Hq, D),
+                         sp::RowMap::attention_side(Hkv, D), softmax_scale, hip_stream);
 }
 
 sp_status sp_attn_fwd_seqlayout(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -189,18 +197,8 @@ sp_status sp_attn_fwd_seqlayout(const void* q, const void* k, const void* v, voi
     if (B == 0 || S_l == 0 || Hq == 0) return SP_OK;
     const int32_t lg = seq_chunk_log2(S_l);
     if (lg < 0) return SP_ERR_UNSUPPORTED;
-    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
-    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
-        !sp::aligned16(lse))
-        return SP_ERR_ALIGN;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
-    a.B = (int32_t)B; a.S = (int32_t)(S_l * P); a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = a.S; a.off = 0;
-    a.qmap = sp::RowMap::sequence_side(lg, Hq, D, P);
-    a.kvmap = sp::RowMap::sequence_side(lg, Hkv, D, P);
-    a.scale = resolve_scale(softmax_scale, D);
-    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+    return run_dense_fwd(q, k, v, o, lse, B, S_l * P, S_l * P, 0, Hq, Hkv, D, sp::RowMap::sequence_side(lg, Hq, D, P),
+                         sp::RowMap::sequence_side(lg, Hkv, D, P), softmax_scale, hip_stream);
 }
 
 sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
@@ -332,17 +330,8 @@ sp_status sp_attn_block_fwd(const void* q, const void* k, const void* v, void* o
     if (st != SP_OK) return st;
     if (B == 0 || Sq == 0 || Hq == 0) return SP_OK;
     if (Skv == 0) return SP_ERR_SHAPE;  // rows that see no key have no softmax
-    if (!q || !k || !v || !o || !lse) return SP_ERR_NULL;
-    if (!sp::aligned16(q) || !sp::aligned16(k) || !sp::aligned16(v) || !sp::aligned16(o) ||
-        !sp::aligned16(lse))
-        return SP_ERR_ALIGN;
-    sp::AttnArgs a{};
-    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
-    a.B = (int32_t)B; a.S = (int32_t)Sq; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
-    a.Skv = (int32_t)Skv; a.off = (int32_t)causal_offset;
-    attention_side_maps(a);
-    a.scale = resolve_scale(softmax_scale, D);
-    return sp::launch_attn_fwd(a, (hipStream_t)hip_stream);
+    return run_dense_fwd(q, k, v, o, lse, B, Sq, Skv, causal_offset, Hq, Hkv, D, sp::RowMap::attention_side(Hq, D),
+                         sp::RowMap::attention_side(Hkv, D), softmax_scale, hip_stream);
 }
 
 size_t sp_attn_block_bwd_workspace_bytes(int64_t B, int64_t Sq, int64_t Skv, int32_t Hq, int32_t Hkv, int32_t D) {
