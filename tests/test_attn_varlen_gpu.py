@@ -108,3 +108,24 @@ def test_varlen_full_size_workload(T, seed):
     e = (rel_l2(host_f64(dq[idx]), r["dQ"]), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
     print(f"varlen T={T} ({len(lengths)} docs): O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
+
+
+@pytest.mark.parametrize("hint", [0, 1, 700, 4000, 10**9])
+def test_varlen_max_seqlen_is_only_a_hint(hint):
+    """max_seqlen shapes the backward's work split and nothing else: exact, too small, too large or absent,
+    the results stay within the parity bars (the forward does not depend on it at all)."""
+    lengths = [700, 1500, 333, 1467]
+    cu = synth.cu_seqlens_from_lengths(lengths)
+    T, Hq, Hkv, D = int(cu[-1]), 4, 1, 128
+    q, k, v, do = synth.attn_inputs(91, T, Hq, Hkv, D)
+    qd, kd, vd, dod = (dev_bf16(t[0]) for t in (q, k, v, do))
+    cud = torch.from_numpy(np.asarray(cu, np.int32)).cuda()
+    o0, lse0 = sp.sp_attn_varlen_fwd(qd, kd, vd, cud)
+    o, lse = sp.sp_attn_varlen_fwd(qd, kd, vd, cud, max_seqlen=min(hint, 2**31 - 1))
+    assert torch.equal(o.view(torch.int16), o0.view(torch.int16)) and torch.equal(lse, lse0)
+    dq, dk, dv = sp.sp_attn_varlen_bwd(qd, kd, vd, o, lse, dod, cud, max_seqlen=min(hint, 2**31 - 1))
+    torch.cuda.synchronize()
+    qf, kf, vf, dof = (rn.widen_bf16(t[0]) for t in (q, k, v, do))
+    dq_r, dk_r, dv_r, _ = rn.attn_varlen_bwd(qf, kf, vf, dof, cu)
+    e = (rel_l2(host_f64(dq), dq_r), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
+    assert max(e) <= GRAD_REL_L2, e
