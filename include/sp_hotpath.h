@@ -105,8 +105,9 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
                       float softmax_scale, void* hip_stream);
 
 /* Bytes of device workspace sp_attn_bwd / sp_attn_varlen_fwd / sp_attn_varlen_bwd
- * need for these extents (T = B*S for the dense call, total tokens for varlen;
- * n_docs = 0 for the dense call).  Returns 0 for invalid arguments. */
+ * need for these extents.  Dense call: pass B and S, n_docs = 0.  Packed
+ * documents: pass the total row count T as S_or_T and n_docs > 0; B is ignored
+ * then (pass 1).  Returns 0 for invalid arguments, B <= 0 included. */
 size_t sp_attn_bwd_workspace_bytes(int64_t B, int64_t S_or_T, int32_t Hq, int32_t Hkv, int32_t D,
                                    int32_t n_docs);
 size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
@@ -114,7 +115,7 @@ size_t sp_attn_varlen_fwd_workspace_bytes(int64_t T, int32_t Hq, int32_t Hkv, in
 
 /* ---------------------------------------------------------------------------
  * Backward of sp_attn_fwd (Section 3.1: the rewritten graph must stay correct
- * in the backward pass; Section 4.4: the backward is where recomputation
+ * in the backward pass; Section 4.2 (breakdown analysis): the backward is where recomputation
  * under activation checkpointing is paid).
  *
  *   inputs : q, k, v, o (as written by the forward), lse, dO [B, S, Hq, D] bf16

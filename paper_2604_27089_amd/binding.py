@@ -117,12 +117,45 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _expect(t: torch.Tensor, shape, dtype, name: str):
+    """The C ABI sees pointers only: extents and element types are checked here, before any launch."""
+    if tuple(t.shape) != tuple(int(x) for x in shape) or t.dtype != dtype:
+        raise ValueError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
+def _new(stream, shape, dtype, device) -> torch.Tensor:
+    """A tensor allocated by a wrapper.  torch's allocator ties a block to the stream that was current when it
+    was allocated; when the kernels go to another stream the block is marked as in use there, so that it is
+    not handed out again while they are still queued."""
+    t = torch.empty(tuple(int(x) for x in shape), dtype=dtype, device=device)
+    if stream is not None:
+        t.record_stream(stream)
+    return t
+
+
+def _attn_shapes(q, k, v, lse_shape, kv_like_q_dims: int, o=None, lse=None, do=None, dq=None, dk=None, dv=None):
+    """bf16 everywhere, k/v agree, the leading `kv_like_q_dims` extents of k equal q's, the head dim agrees."""
+    bf = torch.bfloat16
+    _expect(q, q.shape, bf, "q")
+    kshape = tuple(q.shape[:kv_like_q_dims]) + tuple(k.shape[kv_like_q_dims:-1]) + (q.shape[-1],)
+    _expect(k, kshape, bf, "k")
+    _expect(v, k.shape, bf, "v")
+    for t, like, name in ((o, q, "o"), (do, q, "dO"), (dq, q, "dq"), (dk, k, "dk"), (dv, k, "dv")):
+        if t is not None:
+            _expect(t, like.shape, bf, name)
+    if lse is not None:
+        _expect(lse, lse_shape, torch.float32, "lse")
+
+
 # --------------------------------------------------------------------------- re-layout
 def sp_pack_seq_to_head(x: torch.Tensor, P: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """x [B, S_l, H, D] -> out [B, P*S_l, H/P, D]."""
     B, S_l, H, D = x.shape
+    shape = (B, P * S_l, H // P if P > 0 else H, D)
     if out is None:
-        out = torch.empty((B, P * S_l, H // max(P, 1) if P > 0 else H, D), dtype=x.dtype, device=x.device)
+        out = _new(stream, shape, x.dtype, x.device)
+    elif P > 0 and H % P == 0:
+        _expect(out, shape, x.dtype, "out")
     _check(lib().sp_pack_seq_to_head(_ptr(x), _ptr(out), B, S_l, H, D, P, x.element_size(), _stream(stream)),
            "sp_pack_seq_to_head")
     return out
@@ -131,9 +164,13 @@ def sp_pack_seq_to_head(x: torch.Tensor, P: int, out: Optional[torch.Tensor] = N
 def sp_unpack_head_to_seq(y: torch.Tensor, P: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """y [B, P*S_l, h, D] -> out [B, S_l, P*h, D]."""
     B, PS, h, D = y.shape
+    if P <= 0 or PS % P != 0:
+        raise ValueError(f"y has {PS} rows, not a multiple of P = {P}")
     S_l, H = PS // P, h * P
     if out is None:
-        out = torch.empty((B, S_l, H, D), dtype=y.dtype, device=y.device)
+        out = _new(stream, (B, S_l, H, D), y.dtype, y.device)
+    else:
+        _expect(out, (B, S_l, H, D), y.dtype, "out")
     _check(lib().sp_unpack_head_to_seq(_ptr(y), _ptr(out), B, S_l, H, D, P, y.element_size(), _stream(stream)),
            "sp_unpack_head_to_seq")
     return out
@@ -144,10 +181,9 @@ def sp_attn_fwd(q, k, v, softmax_scale: float = 0.0, o=None, lse=None, stream=No
     """q [B,S,Hq,D], k,v [B,S,Hkv,D] bf16 -> (o [B,S,Hq,D] bf16, lse [B,Hq,S] fp32)."""
     B, S, Hq, D = q.shape
     Hkv = k.shape[2]
-    if o is None:
-        o = torch.empty_like(q)
-    if lse is None:
-        lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device)
+    _attn_shapes(q, k, v, (B, Hq, S), 2, o=o, lse=lse)
+    o = _new(stream, q.shape, q.dtype, q.device) if o is None else o
+    lse = _new(stream, (B, Hq, S), torch.float32, q.device) if lse is None else lse
     _check(lib().sp_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, S, Hq, Hkv, D,
                              float(softmax_scale), _stream(stream)), "sp_attn_fwd")
     return o, lse
@@ -161,8 +197,14 @@ def sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs) -> int:
     return int(lib().sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs))
 
 
-def _workspace(nbytes: int, device) -> torch.Tensor:
-    return torch.empty((max(int(nbytes), 256),), dtype=torch.uint8, device=device)
+def _workspace(nbytes: int, device, stream=None) -> torch.Tensor:
+    return _new(stream, (max(int(nbytes), 256),), torch.uint8, device)
+
+
+def _grads(stream, q, k, v, dq, dk, dv):
+    return (_new(stream, q.shape, q.dtype, q.device) if dq is None else dq,
+            _new(stream, k.shape, k.dtype, k.device) if dk is None else dk,
+            _new(stream, v.shape, v.dtype, v.device) if dv is None else dv)
 
 
 def sp_attn_bwd(q, k, v, o, lse, do, softmax_scale: float = 0.0, dq=None, dk=None, dv=None,
@@ -170,14 +212,13 @@ def sp_attn_bwd(q, k, v, o, lse, do, softmax_scale: float = 0.0, dq=None, dk=Non
     """Returns (dq, dk, dv), bf16, shaped like q, k, v."""
     B, S, Hq, D = q.shape
     Hkv = k.shape[2]
-    dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(k) if dk is None else dk
-    dv = torch.empty_like(v) if dv is None else dv
+    _attn_shapes(q, k, v, (B, Hq, S), 2, o=o, lse=lse, do=do, dq=dq, dk=dk, dv=dv)
+    dq, dk, dv = _grads(stream, q, k, v, dq, dk, dv)
     if workspace is None:
-        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0), q.device)
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, S, Hq, Hkv, D, 0), q.device, stream)
     _check(lib().sp_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq), _ptr(dk),
-                             _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
-                             float(softmax_scale), _stream(stream)), "sp_attn_bwd")
+                             _ptr(dv), _ptr(workspace), workspace.numel() * workspace.element_size(), B, S, Hq,
+                             Hkv, D, float(softmax_scale), _stream(stream)), "sp_attn_bwd")
     return dq, dk, dv
 
 
@@ -189,20 +230,27 @@ def sp_attn_bwd_stages(q, k, v, o, lse, do, dq, dk, dv, workspace, stages: int, 
     """One or more stages of the backward (bit mask of SP_BWD_STAGE_*); buffers are the caller's."""
     B, S, Hq, D = q.shape
     Hkv = k.shape[2]
+    _attn_shapes(q, k, v, (B, Hq, S), 2, o=o, lse=lse, do=do, dq=dq, dk=dk, dv=dv)
     _check(lib().sp_attn_bwd_stages(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
-                                    _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S, Hq, Hkv, D,
+                                    _ptr(dk), _ptr(dv), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), B, S, Hq, Hkv, D,
                                     float(softmax_scale), int(stages), _stream(stream)), "sp_attn_bwd_stages")
     return dq, dk, dv
 
 
+def _seq_heads(q, k, P: int):
+    if P <= 0 or q.shape[2] % P != 0 or k.shape[2] % P != 0:
+        raise ValueError(f"head counts {q.shape[2]} / {k.shape[2]} are not multiples of P = {P}")
+    return q.shape[2] // P, k.shape[2] // P
+
+
 def sp_attn_fwd_seqlayout(q, k, v, P: int, softmax_scale: float = 0.0, o=None, lse=None, stream=None):
     """Sequence-side tensors q [B,S_l,P*Hq,D], k,v [B,S_l,P*Hkv,D] -> (o [B,S_l,P*Hq,D], lse [B,Hq,P*S_l])."""
-    B, S_l, PHq, D = q.shape
-    Hq, Hkv = PHq // P, k.shape[2] // P
-    if o is None:
-        o = torch.empty_like(q)
-    if lse is None:
-        lse = torch.empty((B, Hq, P * S_l), dtype=torch.float32, device=q.device)
+    B, S_l, _, D = q.shape
+    Hq, Hkv = _seq_heads(q, k, P)
+    _attn_shapes(q, k, v, (B, Hq, P * S_l), 2, o=o, lse=lse)
+    o = _new(stream, q.shape, q.dtype, q.device) if o is None else o
+    lse = _new(stream, (B, Hq, P * S_l), torch.float32, q.device) if lse is None else lse
     _check(lib().sp_attn_fwd_seqlayout(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, S_l, Hq, Hkv, D, P,
                                        float(softmax_scale), _stream(stream)), "sp_attn_fwd_seqlayout")
     return o, lse
@@ -211,15 +259,15 @@ def sp_attn_fwd_seqlayout(q, k, v, P: int, softmax_scale: float = 0.0, o=None, l
 def sp_attn_bwd_seqlayout(q, k, v, o, lse, do, P: int, softmax_scale: float = 0.0, dq=None, dk=None, dv=None,
                           workspace=None, stream=None):
     """Backward on sequence-side tensors; returns (dq, dk, dv) shaped like q, k, v."""
-    B, S_l, PHq, D = q.shape
-    Hq, Hkv = PHq // P, k.shape[2] // P
-    dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(k) if dk is None else dk
-    dv = torch.empty_like(v) if dv is None else dv
+    B, S_l, _, D = q.shape
+    Hq, Hkv = _seq_heads(q, k, P)
+    _attn_shapes(q, k, v, (B, Hq, P * S_l), 2, o=o, lse=lse, do=do, dq=dq, dk=dk, dv=dv)
+    dq, dk, dv = _grads(stream, q, k, v, dq, dk, dv)
     if workspace is None:
-        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, P * S_l, Hq, Hkv, D, 0), q.device)
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(B, P * S_l, Hq, Hkv, D, 0), q.device, stream)
     _check(lib().sp_attn_bwd_seqlayout(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
-                                       _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(), B, S_l, Hq, Hkv,
+                                       _ptr(dk), _ptr(dv), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), B, S_l, Hq, Hkv,
                                        D, P, float(softmax_scale), _stream(stream)), "sp_attn_bwd_seqlayout")
     return dq, dk, dv
 
@@ -228,8 +276,9 @@ def sp_attn_block_fwd(q, k, v, causal_offset: int, softmax_scale: float = 0.0, o
     """q [B,Sq,Hq,D], k,v [B,Skv,Hkv,D]; row i sees keys j <= i + causal_offset -> (o, lse [B,Hq,Sq])."""
     B, Sq, Hq, D = q.shape
     Skv, Hkv = k.shape[1], k.shape[2]
-    o = torch.empty_like(q) if o is None else o
-    lse = torch.empty((B, Hq, Sq), dtype=torch.float32, device=q.device) if lse is None else lse
+    _attn_shapes(q, k, v, (B, Hq, Sq), 1, o=o, lse=lse)
+    o = _new(stream, q.shape, q.dtype, q.device) if o is None else o
+    lse = _new(stream, (B, Hq, Sq), torch.float32, q.device) if lse is None else lse
     _check(lib().sp_attn_block_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Sq, Skv, Hq, Hkv, D,
                                    int(causal_offset), float(softmax_scale), _stream(stream)), "sp_attn_block_fwd")
     return o, lse
@@ -239,6 +288,12 @@ def sp_attn_merge(o_acc, lse_acc, o_blk, lse_blk, o_out=None, stream=None):
     """Folds (o_blk bf16, lse_blk) into the running (o_acc fp32 [B,S,Hq,D], lse_acc fp32 [B,Hq,S]) in place;
     also writes the merged O as bf16 into o_out if given."""
     B, S, Hq, D = o_acc.shape
+    _expect(o_acc, (B, S, Hq, D), torch.float32, "o_acc")
+    _expect(lse_acc, (B, Hq, S), torch.float32, "lse_acc")
+    _expect(o_blk, (B, S, Hq, D), torch.bfloat16, "o_blk")
+    _expect(lse_blk, (B, Hq, S), torch.float32, "lse_blk")
+    if o_out is not None:
+        _expect(o_out, (B, S, Hq, D), torch.bfloat16, "o_out")
     _check(lib().sp_attn_merge(_ptr(o_acc), _ptr(lse_acc), _ptr(o_blk), _ptr(lse_blk), _ptr(o_out), B, S, Hq, D,
                                _stream(stream)), "sp_attn_merge")
     return o_acc, lse_acc
@@ -253,16 +308,23 @@ def sp_attn_block_bwd(q, k, v, o, lse, do, causal_offset: int, softmax_scale: fl
     """This block pair's shares (dq, dk, dv), from the final o, lse of the query rows."""
     B, Sq, Hq, D = q.shape
     Skv, Hkv = k.shape[1], k.shape[2]
-    dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(k) if dk is None else dk
-    dv = torch.empty_like(v) if dv is None else dv
+    _attn_shapes(q, k, v, (B, Hq, Sq), 1, o=o, lse=lse, do=do, dq=dq, dk=dk, dv=dv)
+    dq, dk, dv = _grads(stream, q, k, v, dq, dk, dv)
     if workspace is None:
-        workspace = _workspace(sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D), q.device)
+        workspace = _workspace(sp_attn_block_bwd_workspace_bytes(B, Sq, Skv, Hq, Hkv, D), q.device, stream)
     _check(lib().sp_attn_block_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq), _ptr(dk),
-                                   _ptr(dv), _ptr(workspace), workspace.numel(), B, Sq, Skv, Hq, Hkv, D,
-                                   int(causal_offset), float(softmax_scale), int(stages), _stream(stream)),
+                                   _ptr(dv), _ptr(workspace), workspace.numel() * workspace.element_size(), B, Sq,
+                                   Skv, Hq, Hkv, D, int(causal_offset), float(softmax_scale), int(stages),
+                                   _stream(stream)),
            "sp_attn_block_bwd")
     return dq, dk, dv
+
+
+def _docs(cu_seqlens) -> int:
+    if cu_seqlens.dtype != torch.int32 or cu_seqlens.dim() != 1 or cu_seqlens.numel() < 1:
+        raise ValueError(f"cu_seqlens: expected a device int32 vector of n_docs + 1 entries, got "
+                         f"{cu_seqlens.dtype} {tuple(cu_seqlens.shape)}")
+    return cu_seqlens.numel() - 1
 
 
 def sp_attn_varlen_fwd(q, k, v, cu_seqlens, max_seqlen: int = 0, softmax_scale: float = 0.0, o=None,
@@ -270,14 +332,16 @@ def sp_attn_varlen_fwd(q, k, v, cu_seqlens, max_seqlen: int = 0, softmax_scale: 
     """q [T,Hq,D], k,v [T,Hkv,D]; cu_seqlens device int32 [n_docs+1] -> (o, lse [Hq,T])."""
     T, Hq, D = q.shape
     Hkv = k.shape[1]
-    n_docs = cu_seqlens.numel() - 1
-    o = torch.empty_like(q) if o is None else o
-    lse = torch.empty((Hq, T), dtype=torch.float32, device=q.device) if lse is None else lse
+    n_docs = _docs(cu_seqlens)
+    _attn_shapes(q, k, v, (Hq, T), 1, o=o, lse=lse)
+    o = _new(stream, q.shape, q.dtype, q.device) if o is None else o
+    lse = _new(stream, (Hq, T), torch.float32, q.device) if lse is None else lse
     if workspace is None:
-        workspace = _workspace(sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs), q.device)
+        workspace = _workspace(sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs), q.device, stream)
     _check(lib().sp_attn_varlen_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(cu_seqlens), n_docs,
                                     int(max_seqlen), T, Hq, Hkv, D, float(softmax_scale), _ptr(workspace),
-                                    workspace.numel(), _stream(stream)), "sp_attn_varlen_fwd")
+                                    workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sp_attn_varlen_fwd")
     return o, lse
 
 
@@ -285,16 +349,16 @@ def sp_attn_varlen_bwd(q, k, v, o, lse, do, cu_seqlens, max_seqlen: int = 0, sof
                        dq=None, dk=None, dv=None, workspace=None, stream=None):
     T, Hq, D = q.shape
     Hkv = k.shape[1]
-    n_docs = cu_seqlens.numel() - 1
-    dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(k) if dk is None else dk
-    dv = torch.empty_like(v) if dv is None else dv
+    n_docs = _docs(cu_seqlens)
+    _attn_shapes(q, k, v, (Hq, T), 1, o=o, lse=lse, do=do, dq=dq, dk=dk, dv=dv)
+    dq, dk, dv = _grads(stream, q, k, v, dq, dk, dv)
     if workspace is None:
-        workspace = _workspace(sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs), q.device)
+        workspace = _workspace(sp_attn_bwd_workspace_bytes(1, T, Hq, Hkv, D, n_docs), q.device, stream)
     _check(lib().sp_attn_varlen_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(do), _ptr(dq),
                                     _ptr(dk), _ptr(dv), _ptr(cu_seqlens), n_docs, int(max_seqlen), T, Hq,
-                                    Hkv, D, float(softmax_scale), _ptr(workspace), workspace.numel(),
-                                    _stream(stream)), "sp_attn_varlen_bwd")
+                                    Hkv, D, float(softmax_scale), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sp_attn_varlen_bwd")
     return dq, dk, dv
 
 
@@ -302,8 +366,9 @@ def sp_attn_varlen_bwd(q, k, v, o, lse, do, cu_seqlens, max_seqlen: int = 0, sof
 def sp_rmsnorm_fwd(x, w, eps: float, y=None, rstd=None, stream=None):
     """x [T, C] bf16, w [C] bf16 -> (y [T, C] bf16, rstd [T] fp32)."""
     T, C = x.shape
-    y = torch.empty_like(x) if y is None else y
-    rstd = torch.empty((T,), dtype=torch.float32, device=x.device) if rstd is None else rstd
+    _expect(x, (T, C), torch.bfloat16, "x"); _expect(w, (C,), torch.bfloat16, "w")
+    y = _new(stream, x.shape, x.dtype, x.device) if y is None else y
+    rstd = _new(stream, (T,), torch.float32, x.device) if rstd is None else rstd
     _check(lib().sp_rmsnorm_fwd(_ptr(x), _ptr(w), _ptr(y), _ptr(rstd), T, C, float(eps), _stream(stream)), "sp_rmsnorm_fwd")
     return y, rstd
 
@@ -315,33 +380,39 @@ def sp_rmsnorm_bwd_workspace_bytes(T, C) -> int:
 def sp_rmsnorm_bwd(x, w, rstd, dy, dx=None, dw=None, workspace=None, stream=None):
     """Returns (dx [T, C], dw [C]) bf16."""
     T, C = x.shape
-    dx = torch.empty_like(x) if dx is None else dx
-    dw = torch.empty_like(w) if dw is None else dw
+    _expect(x, (T, C), torch.bfloat16, "x"); _expect(w, (C,), torch.bfloat16, "w")
+    _expect(dy, (T, C), torch.bfloat16, "dy"); _expect(rstd, (T,), torch.float32, "rstd")
+    dx = _new(stream, x.shape, x.dtype, x.device) if dx is None else dx
+    dw = _new(stream, w.shape, w.dtype, w.device) if dw is None else dw
     if workspace is None:
-        workspace = _workspace(sp_rmsnorm_bwd_workspace_bytes(T, C), x.device)
+        workspace = _workspace(sp_rmsnorm_bwd_workspace_bytes(T, C), x.device, stream)
     _check(lib().sp_rmsnorm_bwd(_ptr(x), _ptr(w), _ptr(rstd), _ptr(dy), _ptr(dx), _ptr(dw), _ptr(workspace),
-                                workspace.numel(), T, C, _stream(stream)), "sp_rmsnorm_bwd")
+                                workspace.numel() * workspace.element_size(), T, C, _stream(stream)), "sp_rmsnorm_bwd")
     return dx, dw
 
 
 def sp_rope(x, cos_table, sin_table, conjugate: bool = False, out=None, stream=None):
     """x [T, H, D] bf16, cos/sin tables [T, D/2] fp32 -> rotated tensor (out may be x)."""
     T, H, D = x.shape
-    out = torch.empty_like(x) if out is None else out
+    _expect(x, (T, H, D), torch.bfloat16, "x")
+    _expect(cos_table, (T, D // 2), torch.float32, "cos_table"); _expect(sin_table, (T, D // 2), torch.float32, "sin_table")
+    out = _new(stream, x.shape, x.dtype, x.device) if out is None else out
     _check(lib().sp_rope(_ptr(x), _ptr(cos_table), _ptr(sin_table), _ptr(out), T, H, D, int(bool(conjugate)),
                          _stream(stream)), "sp_rope")
     return out
 
 
 def sp_swiglu_fwd(g, u, y=None, stream=None):
-    y = torch.empty_like(g) if y is None else y
+    _expect(g, g.shape, torch.bfloat16, "g"); _expect(u, g.shape, torch.bfloat16, "u")
+    y = _new(stream, g.shape, g.dtype, g.device) if y is None else y
     _check(lib().sp_swiglu_fwd(_ptr(g), _ptr(u), _ptr(y), g.numel(), _stream(stream)), "sp_swiglu_fwd")
     return y
 
 
 def sp_swiglu_bwd(g, u, dy, dg=None, du=None, stream=None):
-    dg = torch.empty_like(g) if dg is None else dg
-    du = torch.empty_like(u) if du is None else du
+    _expect(g, g.shape, torch.bfloat16, "g"); _expect(u, g.shape, torch.bfloat16, "u"); _expect(dy, g.shape, torch.bfloat16, "dy")
+    dg = _new(stream, g.shape, g.dtype, g.device) if dg is None else dg
+    du = _new(stream, u.shape, u.dtype, u.device) if du is None else du
     _check(lib().sp_swiglu_bwd(_ptr(g), _ptr(u), _ptr(dy), _ptr(dg), _ptr(du), g.numel(), _stream(stream)), "sp_swiglu_bwd")
     return dg, du
 

@@ -1,6 +1,6 @@
 // Causal grouped-query attention, backward, for one device's head shard
 // (paper Section 3.1: the rewritten graph must stay correct in the backward
-// pass, each inserted operator having a gradient; Section 4.4: under
+// pass, each inserted operator having a gradient; Section 4.2 (breakdown analysis): under
 // activation checkpointing the backward is where the extra time goes).
 //
 // Three stages, no atomics (bitwise reproducible):

@@ -1,5 +1,5 @@
 // dK and dV of causal grouped-query attention (paper Section 3.1: the rewritten
-// graph must stay correct in the backward pass; Section 4.4: the backward is
+// graph must stay correct in the backward pass; Section 4.2 (breakdown analysis): the backward is
 // where recomputation under activation checkpointing is paid).
 //
 //   dV_j = sum_{a in group} sum_{i>=j} P_ij dO_i

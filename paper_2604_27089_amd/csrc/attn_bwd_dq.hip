@@ -1,5 +1,5 @@
 // dQ of causal grouped-query attention (paper Section 3.1: the rewritten graph
-// must stay correct in the backward pass; Section 4.4: the backward is where
+// must stay correct in the backward pass; Section 4.2 (breakdown analysis): the backward is where
 // recomputation under activation checkpointing is paid).
 //
 //   dQ_i = scale * sum_{j<=i} dS_ij k_j,   dS_ij = P_ij (dO_i.v_j - Delta_i),

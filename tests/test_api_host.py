@@ -148,3 +148,42 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(sp, "LIB_PATH", "/nonexistent/libsp_hotpath.so")
     with pytest.raises(ImportError):
         sp.lib()
+
+
+def test_binding_rejects_wrong_dtypes_and_shapes_before_any_launch():
+    """The C ABI sees pointers only; the wrappers check element types and extents first (CPU tensors suffice:
+    the checks run before any pointer is taken)."""
+    import torch
+
+    bf = torch.bfloat16
+    q = torch.zeros(1, 64, 4, 128, dtype=bf); k = torch.zeros(1, 64, 1, 128, dtype=bf); v = torch.zeros_like(k)
+    with pytest.raises(ValueError, match="q: expected torch.bfloat16"):
+        sp.sp_attn_fwd(q.float(), k, v)
+    with pytest.raises(ValueError, match="k: expected"):
+        sp.sp_attn_fwd(q, k[:, :32], v[:, :32])          # fewer key rows than query rows
+    with pytest.raises(ValueError, match="v: expected"):
+        sp.sp_attn_fwd(q, k, torch.zeros(1, 64, 2, 128, dtype=bf))
+    with pytest.raises(ValueError, match="k: expected"):
+        sp.sp_attn_fwd(q, torch.zeros(1, 64, 1, 64, dtype=bf), torch.zeros(1, 64, 1, 64, dtype=bf))  # head dim
+    with pytest.raises(ValueError, match="lse: expected torch.float32"):
+        sp.sp_attn_fwd(q, k, v, lse=torch.zeros(1, 64, 4))
+    o = torch.zeros_like(q); lse = torch.zeros(1, 4, 64)
+    with pytest.raises(ValueError, match="dO: expected"):
+        sp.sp_attn_bwd(q, k, v, o, lse, torch.zeros(1, 64, 4, 64, dtype=bf))
+    with pytest.raises(ValueError, match="dk: expected"):
+        sp.sp_attn_bwd(q, k, v, o, lse, torch.zeros_like(q), dk=torch.zeros_like(q))
+    qv = q[0]; kv = k[0]
+    with pytest.raises(ValueError, match="cu_seqlens"):
+        sp.sp_attn_varlen_fwd(qv, kv, kv, torch.tensor([0, 64]))  # int64
+    with pytest.raises(ValueError, match="lse: expected"):
+        sp.sp_attn_varlen_fwd(qv, kv, kv, torch.tensor([0, 64], dtype=torch.int32), lse=torch.zeros(64, 4))
+    with pytest.raises(ValueError, match="multiples of P"):
+        sp.sp_attn_fwd_seqlayout(q, k, v, 3)
+    with pytest.raises(ValueError, match="o_blk"):
+        sp.sp_attn_merge(torch.zeros(1, 8, 2, 64), torch.zeros(1, 2, 8), torch.zeros(1, 8, 2, 64), torch.zeros(1, 2, 8))
+    with pytest.raises(ValueError, match="w: expected"):
+        sp.sp_rmsnorm_fwd(torch.zeros(4, 64, dtype=bf), torch.zeros(32, dtype=bf), 1e-5)
+    with pytest.raises(ValueError, match="cos_table"):
+        sp.sp_rope(torch.zeros(4, 2, 64, dtype=bf), torch.zeros(4, 64), torch.zeros(4, 32))
+    with pytest.raises(ValueError, match="u: expected"):
+        sp.sp_swiglu_fwd(torch.zeros(16, dtype=bf), torch.zeros(8, dtype=bf))
