@@ -18,8 +18,10 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+        # REF_STREAM_LIB names another build of ref_stream.c (the sanitizer build of the test suite); it is
+        # loaded as it is and never rebuilt here
+        path = os.environ.get("REF_STREAM_LIB") or _build.LIB
+        if path == _build.LIB and (not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC)):
             _build.build()
         _lib = ctypes.CDLL(path)
         _lib.ref_num_threads.restype = ctypes.c_int

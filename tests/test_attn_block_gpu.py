@@ -9,7 +9,7 @@ from oracle import ref_block as rb
 from oracle import ref_numpy as rn
 from paper_2604_27089_amd import binding as sp
 from paper_2604_27089_amd import synth
-from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, rel_l2
+from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, grad_err
 
 pytestmark = pytest.mark.gpu
 
@@ -164,12 +164,12 @@ def test_ring_of_blocks_matches_oracle(S, n, Hq, Hkv, D):
             rq, rk, rv = rb.block_attn_bwd(q64[a0:a1], k64[c0:c1], v64[c0:c1], lse_ref[:, a0:a1],
                                            delta_ref[:, a0:a1], do64[a0:a1], scale, a0 - c0)
             for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-                err = rel_l2(host_f64(got)[0], ref)
+                err = grad_err(host_f64(got)[0], ref)
                 assert err <= GRAD_REL_L2, f"{name} share of rows {a0}.. keys {c0}..: rel L2 {err:.3e}"
             dq_sum[a0:a1] += host_f64(dq)[0]; dk_sum[c0:c1] += host_f64(dk)[0]; dv_sum[c0:c1] += host_f64(dv)[0]
     fq, fk, fv, _ = rn.attn_bwd(q64, k64, v64, do64)
     for name, got, ref in (("dq", dq_sum, fq), ("dk", dk_sum, fk), ("dv", dv_sum, fv)):
-        err = rel_l2(got, ref)
+        err = grad_err(got, ref)
         assert err <= GRAD_REL_L2, f"{name} summed over blocks: rel L2 {err:.3e}"
 
 
@@ -196,7 +196,7 @@ def test_block_bwd_rectangular_matches_oracle(Sq, Skv, Hq, Hkv, D, off):
     delta_ref = np.einsum("shd,shd->hs", o_ref, do64)
     rq, rk, rv = rb.block_attn_bwd(q64, k64, v64, lse_ref, delta_ref, do64, scale, off)
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-        err = rel_l2(host_f64(got)[0], ref)
+        err = grad_err(host_f64(got)[0], ref)
         assert err <= GRAD_REL_L2, f"{name}: rel L2 {err:.3e}"
 
 
@@ -224,7 +224,7 @@ def test_block_step_full_size_sampled():
     assert np.abs(host_f64(lse[0][:, idx]) - lse_ref).max() <= LSE_MAX_ABS
     delta_ref = np.einsum("shd,shd->hs", o_ref, do64)
     rq, rk, rv = rb.block_attn_bwd(q64, k64, v64, lse_ref, delta_ref, do64, scale, n)
-    e = (rel_l2(host_f64(dq[0, idx]), rq), rel_l2(host_f64(dk)[0], rk), rel_l2(host_f64(dv)[0], rv))
+    e = (grad_err(host_f64(dq[0, idx]), rq), grad_err(host_f64(dk)[0], rk), grad_err(host_f64(dv)[0], rv))
     print(f"ring block {n}x{n}: {rows.size} active rows, rel-L2 dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert max(e) <= GRAD_REL_L2
     mask = torch.ones(n, dtype=torch.bool, device="cuda"); mask[idx] = False

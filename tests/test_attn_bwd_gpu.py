@@ -7,7 +7,7 @@ from oracle import ref_numpy as rn
 from oracle import ref_stream as rs
 from paper_2604_27089_amd import binding as sp
 from paper_2604_27089_amd import synth
-from gpu_util import GRAD_REL_L2, dev_bf16, host_f64, rel_l2
+from gpu_util import GRAD_REL_L2, dev_bf16, host_f64, grad_err
 
 pytestmark = pytest.mark.gpu
 
@@ -42,7 +42,7 @@ def test_bwd_matches_oracle(S, Hq, Hkv, D, B):
     _, _, dq, dk, dv = gpu_fwd_bwd(q, k, v, do)
     for b in range(B):
         dq_r, dk_r, dv_r, _ = rn.attn_bwd(*(rn.widen_bf16(t[b]) for t in (q, k, v, do)))
-        errs = [rel_l2(host_f64(x)[b], r) for x, r in ((dq, dq_r), (dk, dk_r), (dv, dv_r))]
+        errs = [grad_err(host_f64(x)[b], r) for x, r in ((dq, dq_r), (dk, dk_r), (dv, dv_r))]
         print(f"S={S} Hq={Hq} Hkv={Hkv} D={D} b={b}: rel-L2 dQ {errs[0]:.2e} dK {errs[1]:.2e} dV {errs[2]:.2e}")
         if S == 1:  # a single key: dQ = dK = 0 up to fp32 cancellation noise in dP - Delta
             zq, zk = float(np.abs(host_f64(dq)[b]).max()), float(np.abs(host_f64(dk)[b]).max())
@@ -60,9 +60,9 @@ def test_bwd_scale_determinism_and_invariants():
     for a, b in ((dq, dq2), (dk, dk2), (dv, dv2)):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))  # no atomics: bitwise reproducible
     dq_r, dk_r, dv_r, _ = rn.attn_bwd(*(rn.widen_bf16(t[0]) for t in (q, k, v, do)), 0.11)
-    assert rel_l2(host_f64(dq)[0], dq_r) <= GRAD_REL_L2
-    assert rel_l2(host_f64(dk)[0], dk_r) <= GRAD_REL_L2
-    assert rel_l2(host_f64(dv)[0], dv_r) <= GRAD_REL_L2
+    assert grad_err(host_f64(dq)[0], dq_r) <= GRAD_REL_L2
+    assert grad_err(host_f64(dk)[0], dk_r) <= GRAD_REL_L2
+    assert grad_err(host_f64(dv)[0], dv_r) <= GRAD_REL_L2
     # softmax weights sum to one: sum_j dV_j = sum over the group's rows of dO
     G = Hq // Hkv
     want = rn.widen_bf16(do[0]).reshape(S, Hkv, G, D).sum(axis=(0, 2))
@@ -110,7 +110,7 @@ def test_bwd_full_size_sparse_dO(name, n_rows):
     r = rs.attn_rows(qf, kf, vf, rows, dof)
     dk_r, dv_r = rs.attn_cols(qf, kf, vf, dof, rows, r["lse"], r["delta"], np.arange(S))
     dqg, dkg, dvg = host_f64(dq)[0], host_f64(dk)[0], host_f64(dv)[0]
-    e = (rel_l2(dqg[rows], r["dQ"]), rel_l2(dkg, dk_r), rel_l2(dvg, dv_r))
+    e = (grad_err(dqg[rows], r["dQ"]), grad_err(dkg, dk_r), grad_err(dvg, dv_r))
     print(f"{name}: {rows.size} active rows, rel-L2 dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert max(e) <= GRAD_REL_L2
     mask = np.ones(S, bool); mask[rows] = False
@@ -128,13 +128,13 @@ def test_bwd_full_size_dense_dO_sampled(name):
     qf, kf, vf, dof = (rn.widen_bf16(t[0]) for t in (q, k, v, do))
     rows = sparse_rows(S, 20, 3)
     r = rs.attn_rows(qf, kf, vf, rows, dof)
-    e_dq = rel_l2(host_f64(dq[0, torch.from_numpy(rows).cuda()]), r["dQ"])
+    e_dq = grad_err(host_f64(dq[0, torch.from_numpy(rows).cuda()]), r["dQ"])
     W = 160  # tail window: columns j >= S-W are seen by rows j..S-1 only
     tail = np.arange(S - W, S)
     rt = rs.attn_rows(qf, kf, vf, tail, dof)
     dk_r, dv_r = rs.attn_cols(qf, kf, vf, dof, tail, rt["lse"], rt["delta"], tail)
-    e_dk = rel_l2(host_f64(dk[0, S - W:]), dk_r)
-    e_dv = rel_l2(host_f64(dv[0, S - W:]), dv_r)
+    e_dk = grad_err(host_f64(dk[0, S - W:]), dk_r)
+    e_dv = grad_err(host_f64(dv[0, S - W:]), dv_r)
     print(f"{name}: rel-L2 dQ(sampled) {e_dq:.2e} dK(tail) {e_dk:.2e} dV(tail) {e_dv:.2e}")
     assert max(e_dq, e_dk, e_dv) <= GRAD_REL_L2
     want = dof.reshape(S, Hkv, Hq // Hkv, D).sum(axis=(0, 2))

@@ -10,7 +10,7 @@ from oracle import ref_block as rb
 from oracle import ref_numpy as rn
 from paper_2604_27089_amd import binding as sp
 from paper_2604_27089_amd import synth
-from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, rel_l2
+from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, grad_err
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +45,7 @@ def test_random_causal_fwd_bwd(seed):
         assert np.abs(host_f64(lse)[b] - lse_ref).max() <= LSE_MAX_ABS
         rq, rk, rv, _ = rn.attn_bwd(*f, scale)
         for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            err = rel_l2(host_f64(got)[b], ref)
+            err = grad_err(host_f64(got)[b], ref)
             assert err <= GRAD_REL_L2, f"{name} S={S} Hq={Hq} Hkv={Hkv} D={D} b={b}: rel L2 {err:.3e}"
 
 
@@ -70,7 +70,7 @@ def test_random_block_fwd_bwd(seed):
     delta_ref = np.einsum("shd,shd->hs", o_ref, do64)
     rq, rk, rv = rb.block_attn_bwd(q64, k64, v64, lse_ref, delta_ref, do64, scale, off)
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-        err = rel_l2(host_f64(got)[0], ref)
+        err = grad_err(host_f64(got)[0], ref)
         assert err <= GRAD_REL_L2, f"{name} {what}: rel L2 {err:.3e}"
 
 
@@ -96,5 +96,5 @@ def test_random_packed_documents(seed):
     assert np.abs(host_f64(lse) - lse_ref).max() <= LSE_MAX_ABS, what
     rq, rk, rv, _ = rn.attn_varlen_bwd(*f, cu_h)
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-        err = rel_l2(host_f64(got), ref)
+        err = grad_err(host_f64(got), ref)
         assert err <= GRAD_REL_L2, f"{name} {what}: rel L2 {err:.3e}"

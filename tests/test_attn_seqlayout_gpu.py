@@ -8,7 +8,7 @@ import torch
 from oracle import ref_numpy as rn
 from paper_2604_27089_amd import binding as sp
 from paper_2604_27089_amd import synth
-from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, rel_l2
+from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, grad_err
 
 pytestmark = pytest.mark.gpu
 
@@ -63,7 +63,7 @@ def test_seqlayout_matches_oracle():
     un = lambda x: rn.unpack_head_to_seq(x, P)
     check_o(host_f64(o)[0], un(o_r), "seq-layout O")
     assert np.abs(host_f64(lse)[0] - lse_r).max() <= LSE_MAX_ABS
-    e = (rel_l2(host_f64(dq)[0], un(dq_r)), rel_l2(host_f64(dk)[0], un(dk_r)), rel_l2(host_f64(dv)[0], un(dv_r)))
+    e = (grad_err(host_f64(dq)[0], un(dq_r)), grad_err(host_f64(dk)[0], un(dk_r)), grad_err(host_f64(dv)[0], un(dv_r)))
     print(f"seq-layout: rel-L2 dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert max(e) <= GRAD_REL_L2
 

@@ -7,7 +7,7 @@ from oracle import ref_numpy as rn
 from oracle import ref_stream as rs
 from paper_2604_27089_amd import binding as sp
 from paper_2604_27089_amd import synth
-from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, rel_l2
+from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, dev_bf16, host_f64, grad_err
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +43,7 @@ def test_varlen_matches_oracle(lengths, Hq, Hkv, D):
     dq_r, dk_r, dv_r, _ = rn.attn_varlen_bwd(qf, kf, vf, dof, cu)
     err = check_o(host_f64(o), o_r)
     lerr = np.abs(host_f64(lse) - l_r).max()
-    e = (rel_l2(host_f64(dq), dq_r), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
+    e = (grad_err(host_f64(dq), dq_r), grad_err(host_f64(dk), dk_r), grad_err(host_f64(dv), dv_r))
     print(f"lengths={lengths}: O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert lerr <= LSE_MAX_ABS
     assert max(e) <= GRAD_REL_L2
@@ -105,7 +105,7 @@ def test_varlen_full_size_workload(T, seed):
     idx = torch.from_numpy(rows).cuda()
     err = check_o(host_f64(o[idx]), r["O"])
     lerr = np.abs(host_f64(lse[:, idx]) - r["lse"]).max()
-    e = (rel_l2(host_f64(dq[idx]), r["dQ"]), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
+    e = (grad_err(host_f64(dq[idx]), r["dQ"]), grad_err(host_f64(dk), dk_r), grad_err(host_f64(dv), dv_r))
     print(f"varlen T={T} ({len(lengths)} docs): O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
     assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
 
@@ -127,5 +127,5 @@ def test_varlen_max_seqlen_is_only_a_hint(hint):
     torch.cuda.synchronize()
     qf, kf, vf, dof = (rn.widen_bf16(t[0]) for t in (q, k, v, do))
     dq_r, dk_r, dv_r, _ = rn.attn_varlen_bwd(qf, kf, vf, dof, cu)
-    e = (rel_l2(host_f64(dq), dq_r), rel_l2(host_f64(dk), dk_r), rel_l2(host_f64(dv), dv_r))
+    e = (grad_err(host_f64(dq), dq_r), grad_err(host_f64(dk), dk_r), grad_err(host_f64(dv), dv_r))
     assert max(e) <= GRAD_REL_L2, e
