@@ -24,8 +24,9 @@
  *   - Errors are return codes.  Argument errors are found before any launch
  *     (no GPU is needed to get them); a failed launch gives SP_ERR_LAUNCH.
  *   - Empty problems (a zero extent) return SP_OK without launching.
- *   - No global mutable state: calls from several host threads are safe as
- *     long as they do not share output or workspace buffers.
+ *   - No global mutable state (sp_attn_varlen_fwd_static excepted, see there):
+ *     calls from several host threads are safe as long as they do not share
+ *     output or workspace buffers.
  *   - bf16 tensors are `uint16_t`-sized elements passed as `const void*`.
  */
 #ifndef SP_HOTPATH_H
@@ -257,6 +258,24 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
                              const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
                              int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* sp_attn_varlen_fwd for callers that cannot allocate device memory at all, not
+ * even a workspace: code recorded into a HIP graph, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments minus the workspace, same kernels, same
+ * bits.  The document windows and tile orders go to a scratch array of 8 MiB
+ * (8,388,608 bytes) that is part of the loaded library: every device the library
+ * runs on holds one copy until the process ends.  A problem whose
+ * sp_attn_varlen_fwd_workspace_bytes(...) exceeds that size (about one million
+ * rows) gets SP_ERR_WORKSPACE and launches nothing.  The first call on a device
+ * looks up that device's copy (no allocation); SP_ERR_UNSUPPORTED for a device
+ * ordinal above 63.  All calls on one device share the one array: calls that
+ * may overlap in time on one device (two streams, two host threads) race on it
+ * and must be serialised by the caller; calls ordered on one stream are safe,
+ * each call rewrites every word it later reads. */
+sp_status sp_attn_varlen_fwd_static(const void* q, const void* k, const void* v, void* o, float* lse,
+                                    const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                                    int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                                    void* hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Pointwise operators between the matrix multiplications of a Llama layer, on

@@ -23,7 +23,7 @@ SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_A
 EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
     "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
-    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
+    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_varlen_fwd_static", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
     "sp_attn_block_fwd", "sp_attn_merge", "sp_attn_block_bwd_workspace_bytes", "sp_attn_block_bwd",
     "sp_rmsnorm_bwd_workspace_bytes", "sp_rmsnorm_fwd", "sp_rmsnorm_bwd", "sp_rope", "sp_swiglu_fwd", "sp_swiglu_bwd",
 )
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_block_bwd.argtypes = [vp] * 10 + [sz, i64, i64, i64, i32, i32, i32, i64, f32, i32, vp]
     L.sp_attn_varlen_fwd.restype = c.c_int
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
+    L.sp_attn_varlen_fwd_static.restype = c.c_int
+    L.sp_attn_varlen_fwd_static.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
     L.sp_attn_varlen_bwd.argtypes = [vp] * 10 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_rmsnorm_bwd_workspace_bytes.restype = sz
@@ -342,6 +344,18 @@ def sp_attn_varlen_fwd(q, k, v, cu_seqlens, max_seqlen: int = 0, softmax_scale: 
                                     int(max_seqlen), T, Hq, Hkv, D, float(softmax_scale), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)),
            "sp_attn_varlen_fwd")
+    return o, lse
+
+
+def sp_attn_varlen_fwd_static(q, k, v, cu_seqlens, o, lse, max_seqlen: int = 0, softmax_scale: float = 0.0, stream=None):
+    """sp_attn_varlen_fwd on the library's own static scratch: allocates nothing, so o and lse are the caller's."""
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    n_docs = _docs(cu_seqlens)
+    _attn_shapes(q, k, v, (Hq, T), 1, o=o, lse=lse)
+    _check(lib().sp_attn_varlen_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(cu_seqlens), n_docs,
+                                           int(max_seqlen), T, Hq, Hkv, D, float(softmax_scale), _stream(stream)),
+           "sp_attn_varlen_fwd_static")
     return o, lse
 
 

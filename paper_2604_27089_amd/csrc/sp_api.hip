@@ -1,6 +1,9 @@
 // C-ABI entry points: argument validation on the host, then kernel launches on
-// the caller's stream.  Nothing here allocates, frees or synchronises.
+// the caller's stream.  Nothing here allocates, frees or synchronises.  The only
+// state kept between calls is the per-device address of one static scratch array.
 #include <math.h>
+
+#include <mutex>
 
 #include "sp_common.h"
 
@@ -143,7 +146,7 @@ const char* sp_status_str(sp_status s) {
     return "SP_ERR_?: unknown status";
 }
 
-int32_t sp_abi_version(void) { return 3; }
+int32_t sp_abi_version(void) { return 4; }
 
 sp_status sp_pack_seq_to_head(const void* in, void* out, int64_t B, int64_t S_l, int64_t H,
                               int64_t D, int32_t P, int32_t elem_bytes, void* hip_stream) {
@@ -240,27 +243,16 @@ sp_status sp_attn_bwd_seqlayout(const void* q, const void* k, const void* v, con
                          sp::RowMap::sequence_side(lg, Hkv, D, P), softmax_scale, SP_BWD_STAGE_ALL, hip_stream);
 }
 
-sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
-                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
-                             void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)max_seqlen;
-    if (n_docs < 0) return SP_ERR_SHAPE;
-    sp_status st = check_attn_shape(1, T, Hq, Hkv, D);
-    if (st != SP_OK) return st;
-    if (T == 0 || Hq == 0) return SP_OK;
-    if (n_docs == 0) return SP_ERR_SHAPE;  // T > 0 rows must belong to some document
-    if (!q || !k || !v || !o || !lse || !cu_seqlens || !workspace) return SP_ERR_NULL;
-    const void* ptrs[] = {q, k, v, o, lse, workspace};
-    for (const void* p : ptrs)
-        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return SP_ERR_ALIGN;
-    if (workspace_bytes < sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)hip_stream;
+namespace {
+// common body of the two packed-document forward entry points; `workspace` holds at least
+// sp_attn_varlen_fwd_workspace_bytes(...) bytes
+sp_status run_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                         const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                         float softmax_scale, void* workspace, hipStream_t s) {
     int32_t* row_lo = (int32_t*)workspace;
     int32_t* row_hi = (int32_t*)((char*)workspace + bounds_bytes(T));
     sp::AttnArgs a{};
-    st = make_bounds(a, cu_seqlens, n_docs, T, row_lo, row_hi, (char*)row_hi + bounds_bytes(T), s);
+    sp_status st = make_bounds(a, cu_seqlens, n_docs, T, row_lo, row_hi, (char*)row_hi + bounds_bytes(T), s);
     if (st != SP_OK) return st;
     a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
     a.B = 1; a.S = (int32_t)T; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
@@ -268,6 +260,85 @@ sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* 
     attention_side_maps(a);
     a.scale = resolve_scale(softmax_scale, D);
     return sp::launch_attn_fwd(a, s);
+}
+
+// argument checks shared by the two entry points (everything but the workspace); SP_OK with *empty = true
+// means "nothing to do"
+sp_status check_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                           const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t Hq, int32_t Hkv, int32_t D,
+                           bool* empty) {
+    *empty = false;
+    if (n_docs < 0) return SP_ERR_SHAPE;
+    sp_status st = check_attn_shape(1, T, Hq, Hkv, D);
+    if (st != SP_OK) return st;
+    if (T == 0 || Hq == 0) { *empty = true; return SP_OK; }
+    if (n_docs == 0) return SP_ERR_SHAPE;  // T > 0 rows must belong to some document
+    if (!q || !k || !v || !o || !lse || !cu_seqlens) return SP_ERR_NULL;
+    const void* ptrs[] = {q, k, v, o, lse};
+    for (const void* p : ptrs)
+        if (!sp::aligned16(p)) return SP_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0) return SP_ERR_ALIGN;
+    return SP_OK;
+}
+
+// Scratch of sp_attn_varlen_fwd_static: device memory that belongs to the loaded library, one copy per
+// device, held until the process ends.  In host code the array's name is only a handle; its device address
+// is looked up once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+sp_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SP_ERR_LAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return SP_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SP_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SP_OK;
+}
+}  // namespace
+
+sp_status sp_attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                             const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                             int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)max_seqlen;
+    bool empty = false;
+    sp_status st = check_varlen_fwd(q, k, v, o, lse, cu_seqlens, n_docs, T, Hq, Hkv, D, &empty);
+    if (st != SP_OK || empty) return st;
+    if (!workspace) return SP_ERR_NULL;
+    if (!sp::aligned16(workspace)) return SP_ERR_ALIGN;
+    if (workspace_bytes < sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs)) return SP_ERR_WORKSPACE;
+    return run_varlen_fwd(q, k, v, o, lse, cu_seqlens, n_docs, T, Hq, Hkv, D, softmax_scale, workspace,
+                          (hipStream_t)hip_stream);
+}
+
+sp_status sp_attn_varlen_fwd_static(const void* q, const void* k, const void* v, void* o, float* lse,
+                                    const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,
+                                    int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+                                    void* hip_stream) {
+    (void)max_seqlen;
+    bool empty = false;
+    sp_status st = check_varlen_fwd(q, k, v, o, lse, cu_seqlens, n_docs, T, Hq, Hkv, D, &empty);
+    if (st != SP_OK || empty) return st;
+    if (sp_attn_varlen_fwd_workspace_bytes(T, Hq, Hkv, D, n_docs) > kStaticScratchBytes) return SP_ERR_WORKSPACE;
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != SP_OK) return st;
+    // every word of the scratch that the attention kernel reads is written by the bounds kernels of this
+    // call first, so nothing needs clearing between calls
+    return run_varlen_fwd(q, k, v, o, lse, cu_seqlens, n_docs, T, Hq, Hkv, D, softmax_scale, ws,
+                          (hipStream_t)hip_stream);
 }
 
 sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o,

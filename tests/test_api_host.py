@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
     assert set(names) == set(sp.EXPORTS)
-    assert L.sp_abi_version() == 3
+    assert L.sp_abi_version() == 4
 
 
 def test_status_strings():
