@@ -283,26 +283,40 @@ def main():
         detail["recompute_fwd_tflops"] = fl_fwd / (t * 1e-3) / 1e12
         # re-layout bandwidth on the 70B-shaped Q shard [16384, 64, 128] (cold by size: 537 MB moved)
         pc = synth.CONFIGS["c4_70b_128k"]["pack"]
-        xs = torch.empty((1, pc["S_l"], pc["H"], pc["D"]), **bf).normal_()
-        ys = torch.empty((1, pc["S_l"] * pc["P"], pc["H"] // pc["P"], pc["D"]), **bf)
-        nbytes = 2.0 * xs.numel() * 2
-        tp = time_fn(lambda: sp.sp_pack_seq_to_head(xs, pc["P"], out=ys), 20, 3)
-        tu = time_fn(lambda: sp.sp_unpack_head_to_seq(ys, pc["P"], out=xs), 20, 3)
-        tc = time_fn(lambda: ys.view(-1).copy_(xs.view(-1)), 20, 3)
+        # a ring of three buffer pairs (1.6 GB): no launch finds its source or destination in the 256 MB
+        # memory-side cache
+        ring = 3
+        xr = [torch.empty((1, pc["S_l"], pc["H"], pc["D"]), **bf).normal_() for _ in range(ring)]
+        yr = [torch.empty((1, pc["S_l"] * pc["P"], pc["H"] // pc["P"], pc["D"]), **bf) for _ in range(ring)]
+        nbytes = 2.0 * xr[0].numel() * 2
+        turn = [0]
+
+        def rot(fn):
+            def go():
+                i = turn[0] % ring
+                turn[0] += 1
+                fn(xr[i], yr[i])
+            return go
+        tp = time_fn(rot(lambda x, y: sp.sp_pack_seq_to_head(x, pc["P"], out=y)), 21, 3)
+        tu = time_fn(rot(lambda x, y: sp.sp_unpack_head_to_seq(y, pc["P"], out=x)), 21, 3)
+        tc = time_fn(rot(lambda x, y: y.view(-1).copy_(x.view(-1))), 21, 3)
+        # the same kernel as a plain linear copy (one peer: the permutation is the identity)
+        tl = time_fn(rot(lambda x, y: sp.sp_pack_seq_to_head(x, 1, out=y.view(x.shape))), 21, 3)
         # what this device gives one-directional streams of the same size, from plain library operations:
         # a fill (stores only) and a reduction (loads only)
-        tw = time_fn(lambda: ys.fill_(1.0), 20, 3)
-        xi = xs.view(torch.int32)
-        tr = time_fn(lambda: xi.max(), 20, 3)
+        tw = time_fn(rot(lambda x, y: y.fill_(1.0)), 21, 3)
+        tr = time_fn(rot(lambda x, y: x.view(torch.int32).max()), 21, 3)
         detail["pack"] = {"shape": "[16384,64,128]->[131072,8,128] bf16", "bytes_moved": nbytes,
+                          "buffers": f"ring of {ring} source/destination pairs, cold",
                           "pack_GBps": nbytes / tp / 1e6, "unpack_GBps": nbytes / tu / 1e6,
+                          "same_kernel_linear_copy_GBps": nbytes / tl / 1e6,
                           "device_copy_GBps": nbytes / tc / 1e6,
                           "write_only_GBps": 0.5 * nbytes / tw / 1e6, "read_only_GBps": 0.5 * nbytes / tr / 1e6,
                           "one_directional_note": "torch fill_ / max over one 268 MB tensor (bytes of one direction)",
                           "peak_GBps": HBM_PEAK_GBPS,
                           "pack_frac_of_peak": nbytes / tp / 1e6 / HBM_PEAK_GBPS,
                           "unpack_frac_of_peak": nbytes / tu / 1e6 / HBM_PEAK_GBPS}
-        del xs, ys
+        del xr, yr
         # packed variable-length documents, T = 65536
         vc = synth.CONFIGS["c5_varlen_64k"]
         T = vc["T"]

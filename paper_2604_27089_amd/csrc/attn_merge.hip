@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(float* __restrict__ o_a
                                                         const __bf16* __restrict__ o_blk,
                                                         const float* __restrict__ lse_blk, __bf16* __restrict__ o_out,
                                                         int64_t n_vec, int32_t S, int32_t Hq) {
-    constexpr int LPV = D / 8;  // lanes per (row, head) vector, 8 elements each
+    constexpr int LPV = D / 4;  // lanes per (row, head) vector, 4 elements each: a wave's fp32 loads and stores
+                                // are 1 KB contiguous (8 elements per lane would stride them by 32 bytes)
     const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;  // (b*S + i)*Hq + h
     const int part = threadIdx.x % LPV;
     if (vec >= n_vec) return;
@@ -35,23 +36,19 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(float* __restrict__ o_a
         wa = ea * inv; wb = eb * inv;
         l = m + logf(ea + eb);
     }
-    const size_t at = (size_t)vec * D + 8 * part;
+    const size_t at = (size_t)vec * D + 4 * part;
+    // plain accesses on purpose: O_acc is updated in place, and non-temporal loads and stores of the same
+    // lines measured 6 % slower
     const f32x4 a0 = *reinterpret_cast<const f32x4*>(o_acc + at);
-    const f32x4 a1 = *reinterpret_cast<const f32x4*>(o_acc + at + 4);
-    const bf16x8 bb = as_bf16x8(*reinterpret_cast<const u32x4*>(o_blk + at));
-    f32x4 r0, r1;
+    const bf16x4 bb = __builtin_bit_cast(bf16x4, *reinterpret_cast<const u32x2*>(o_blk + at));
+    f32x4 r0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        r0[e] = wa * a0[e] + wb * (float)bb[e];
-        r1[e] = wa * a1[e] + wb * (float)bb[4 + e];
-    }
+    for (int e = 0; e < 4; ++e) r0[e] = wa * a0[e] + wb * (float)bb[e];
     *reinterpret_cast<f32x4*>(o_acc + at) = r0;
-    *reinterpret_cast<f32x4*>(o_acc + at + 4) = r1;
     if (o_out) {
-        u32x4 w;
+        u32x2 w;
         w[0] = pack_bf16(r0[0], r0[1]); w[1] = pack_bf16(r0[2], r0[3]);
-        w[2] = pack_bf16(r1[0], r1[1]); w[3] = pack_bf16(r1[2], r1[3]);
-        *reinterpret_cast<u32x4*>(o_out + at) = w;
+        *reinterpret_cast<u32x2*>(o_out + at) = w;
     }
     // every lane of the vector has read LSE_acc above (the lanes of a vector sit in one wave)
     if (part == 0) lse_acc[li] = l;
@@ -64,7 +61,7 @@ namespace sp {
 sp_status launch_attn_merge(float* o_acc, float* lse_acc, const void* o_blk, const float* lse_blk, void* o_out,
                             int64_t B, int64_t S, int32_t Hq, int32_t D, hipStream_t st) {
     const int64_t n_vec = B * S * Hq;
-    const int64_t blocks = (n_vec * (D / 8) + 255) / 256;
+    const int64_t blocks = (n_vec * (D / 4) + 255) / 256;
     if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
     if (D == 128)
         hipLaunchKernelGGL((attn_merge_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, st, o_acc, lse_acc,

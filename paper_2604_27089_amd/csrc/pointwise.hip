@@ -119,18 +119,27 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const __bf16* __restri
         wv[j] = *reinterpret_cast<const u32x4*>(w + (c0 < C ? c0 : C - 8));
         if (c0 >= C) wv[j] = u32x4{0, 0, 0, 0};
     }
-    int par = 0;
-    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, par ^= 1) {
+    // The next row's x and dy are requested before this row's sum goes through the barrier, so a
+    // workgroup always has two rows of loads in flight (one row at a time left the memory system idle
+    // during every reduction: 4.5 TB/s).
+    auto fetch = [&](int64_t row, u32x4 (&xn)[NVT], u32x4 (&dn)[NVT]) __attribute__((always_inline)) {
         const __bf16* xr = x + row * C;
         const __bf16* dyr = dy + row * C;
-        u32x4 xv[NVT], dv[NVT];
 #pragma unroll
         for (int j = 0; j < NVT; ++j) {
             const int c0 = (j * 256 + (int)threadIdx.x) * 8;
             const int cc = c0 < C ? c0 : C - 8;
-            xv[j] = ld16(xr + cc);
-            dv[j] = ld16(dyr + cc);
+            xn[j] = ld16(xr + cc);
+            dn[j] = ld16(dyr + cc);
         }
+    };
+    u32x4 xv[NVT], dv[NVT], xn[NVT], dn[NVT];
+    if ((int64_t)blockIdx.x < T) fetch(blockIdx.x, xn, dn);
+    int par = 0;
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, par ^= 1) {
+#pragma unroll
+        for (int j = 0; j < NVT; ++j) { xv[j] = xn[j]; dv[j] = dn[j]; }
+        if (row + gridDim.x < T) fetch(row + gridDim.x, xn, dn);
         const float r = rstd[row];
         float dot = 0.f;
 #pragma unroll
@@ -144,7 +153,10 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const __bf16* __restri
         }
         dot = wave_sum(dot);
         if (lane == 0) wsum[par][wave] = dot;
-        __syncthreads();  // the other parity's slots are free again: everybody read them before this barrier
+        // Workgroup barrier that waits for the LDS write only: a full __syncthreads() would also wait for the
+        // next row's loads, which are meant to stay in flight across it.  The other parity's slots are free
+        // again: everybody read them before this barrier.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         dot = (wsum[par][0] + wsum[par][1]) + (wsum[par][2] + wsum[par][3]);
         const float coef = r * r * r * dot / (float)C;
         __bf16* dxr = dx + row * C;
@@ -174,23 +186,33 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const __bf16* __restri
     }
 }
 
-// dw[c] = sum of the partial rows, in a fixed order: a block takes 16 columns, its 16 thread rows take every
-// sixteenth partial row each, and their sums are added in thread-row order through LDS
+// dw[c] = sum of the partial rows, in a fixed order.  A block takes 64 columns: 16 threads across (four
+// columns, one 16-byte load each) by 16 thread rows; thread row k adds partial rows k, k+16, ... (all its
+// loads independent, so they are in flight together), and the 16 sums are added in thread-row order
+// through LDS.  Every load instruction of a wave covers whole 256-byte row segments.
 __global__ __launch_bounds__(256) void rmsnorm_dw_kernel(const float* __restrict__ part, __bf16* __restrict__ dw,
                                                         int32_t n_part, int32_t C) {
-    __shared__ float red[16][17];
+    __shared__ f32x4 red[16][16];
     const int cl = threadIdx.x & 15, pl = threadIdx.x >> 4;
-    const int c = blockIdx.x * 16 + cl;
-    float s = 0.f;
-    if (c < C)
-        for (int i = pl; i < n_part; i += 16) s += part[(size_t)i * C + c];
+    const int c = blockIdx.x * 64 + cl * 4;  // C is a multiple of 8, so a quad is inside the row or outside it
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (c < C) {
+#pragma unroll 8
+        for (int i = pl; i < n_part; i += 16) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)i * C + c);
+            s += v;
+        }
+    }
     red[pl][cl] = s;
     __syncthreads();
     if (pl == 0 && c < C) {
-        float t = 0.f;
+        f32x4 t = red[0][cl];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) t += red[k][cl];
-        dw[c] = (__bf16)t;
+        for (int k = 1; k < 16; ++k) t += red[k][cl];
+        const f32x2 lo = {t[0], t[1]}, hi = {t[2], t[3]};
+        uint32_t w[2] = {__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2)),
+                         __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2))};
+        *reinterpret_cast<uint2*>(dw + c) = uint2{w[0], w[1]};
     }
 }
 
@@ -264,12 +286,16 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const __bf16* __restric
 }
 
 inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+#ifndef SP_RMS_BWD_GROUPS
+#define SP_RMS_BWD_GROUPS 512
+#endif
+constexpr int kRmsBwdGroups = SP_RMS_BWD_GROUPS;  // workgroups of the RMS-norm backward = partial rows of dw
 
 }  // namespace
 
 namespace sp {
 
-int32_t rmsnorm_bwd_groups(int64_t T) { return (int32_t)(T < 1024 ? (T < 1 ? 1 : T) : 1024); }
+int32_t rmsnorm_bwd_groups(int64_t T) { return (int32_t)(T < kRmsBwdGroups ? (T < 1 ? 1 : T) : kRmsBwdGroups); }
 
 sp_status launch_rmsnorm_fwd(const void* x, const void* w, void* y, float* rstd, int64_t T, int32_t C, float eps,
                              hipStream_t st) {
@@ -291,7 +317,7 @@ sp_status launch_rmsnorm_bwd(const void* x, const void* w, const float* rstd, co
     if (nv <= 1) SP_RMS_BWD(1); else if (nv <= 2) SP_RMS_BWD(2); else if (nv <= 4) SP_RMS_BWD(4); else return SP_ERR_UNSUPPORTED;
 #undef SP_RMS_BWD
     if (launch_status() != SP_OK) return SP_ERR_LAUNCH;
-    hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3(blocks_for(C, 16)), dim3(256), 0, st, part, (__bf16*)dw, groups, C);
+    hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3(blocks_for(C, 64)), dim3(256), 0, st, part, (__bf16*)dw, groups, C);
     return launch_status();
 }
 

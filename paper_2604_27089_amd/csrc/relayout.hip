@@ -63,24 +63,29 @@ __global__ __launch_bounds__(kThreads) void relayout_kernel(const u32x4* __restr
         if (dst[u] < (IDX)n_vec) __builtin_nontemporal_store(val[u], out + (size_t)dst[u]);
 }
 
-// Fast path for power-of-two runs (every workload shape): no divisions.  One workgroup moves
-// kThreads*kUnroll consecutive vectors of one (batch, peer) slab of the head-side tensor, which is
+// Fast path for power-of-two runs (every workload shape): no divisions by the run.  One workgroup moves
+// kFastThreads*UNROLL consecutive vectors of one (batch, peer) slab of the head-side tensor, which is
 // contiguous there; on the sequence side the same vectors are S_l runs strided by P*run.
-// grid = (ceil(S_l*run / (kFastThreads*UNROLL)), P, B).  Block and unroll sizes come from a sweep
-// on MI355X: 512 threads with two vectors in flight each reach 5.9 TB/s on long runs (2 KB), four
-// vectors suit the 256-byte runs of K/V better; deeper unrolling loses up to 35 %.
+// grid.x = peer + P * chunk, grid.y = batch: the PEER varies fastest, so that the workgroups in flight
+// together touch whole rows of the sequence-side tensor (P adjacent runs) instead of one run out of
+// every P.  With the chunk fastest, a slab's reads land on one out of every P address granules at a time
+// and leave most memory channels idle in turn: 6.0 TB/s against 6.5 on the 70B-shaped Q shard, where a
+// plain linear copy of the same bytes reaches 6.5.  Block and unroll sizes come from a sweep on MI355X
+// with cold buffers: one 16-byte vector per thread and 512 threads; more vectors in flight per thread lose
+// 4 % (two) to 9 % (four).
 constexpr int kFastThreads = 512;
+constexpr int kFastUnroll = 1;
 template <bool TO_HEAD, int UNROLL>
 __global__ __launch_bounds__(kFastThreads) void relayout_pow2_kernel(const u32x4* __restrict__ in,
                                                                 u32x4* __restrict__ out, uint32_t slab_vec,
                                                                 uint32_t log2_run, uint32_t S_l, uint32_t P) {
-    const uint32_t p = blockIdx.y, b = blockIdx.z;
+    const uint32_t chunk = blockIdx.x / P, p = blockIdx.x - chunk * P, b = blockIdx.y;
     const uint32_t run_mask = (1u << log2_run) - 1u;
     const size_t batch_vec = (size_t)slab_vec * P;  // vectors per batch element
     const u32x4* src = in + (size_t)b * batch_vec;
     u32x4* dst = out + (size_t)b * batch_vec;
     const uint32_t head_base = p * slab_vec;        // slab p of the head-side tensor
-    const uint32_t e0 = blockIdx.x * (kFastThreads * UNROLL) + threadIdx.x;
+    const uint32_t e0 = chunk * (kFastThreads * UNROLL) + threadIdx.x;
     u32x4 val[UNROLL];
     uint32_t to[UNROLL];
 #pragma unroll
@@ -99,10 +104,9 @@ __global__ __launch_bounds__(kFastThreads) void relayout_pow2_kernel(const u32x4
 
 // Unpack with linear stores: one workgroup writes kFastThreads*UNROLL consecutive vectors of the
 // sequence-side tensor and gathers them from the P slabs of the head-side tensor (runs and P powers of
-// two).  Stores are the slower direction of the memory system (a write-only stream reaches 5.6 TB/s on
-// MI355X, a read-only one 7.1), so for long runs the unpack keeps its stores contiguous and scatters its
-// loads instead: 5.7 against 5.3 TB/s on 2 KB runs; on 256-byte runs the slab-wise kernel above stays
-// ahead.  grid = (ceil(P*S_l*run / (kFastThreads*UNROLL)), B).
+// two): both sides of the copy then advance through whole rows.  Used for runs of 2 KB and more (6.3 TB/s
+// on the 70B-shaped Q shard); on shorter runs the slab-wise kernel above is as fast.
+// grid = (ceil(P*S_l*run / (kFastThreads*UNROLL)), B).
 template <int UNROLL>
 __global__ __launch_bounds__(kFastThreads) void unpack_pow2_linear_store_kernel(const u32x4* __restrict__ in,
                                                                            u32x4* __restrict__ out,
@@ -144,28 +148,25 @@ sp_status launch_relayout(const void* in, void* out, int64_t B, int64_t S_l, int
     if ((run & (run - 1)) == 0 && slab * (uint64_t)P + 4096 < 0xffffffffull && P <= 65535 && B <= 65535) {
         uint32_t lr = 0;
         while ((1ull << lr) < run) ++lr;
-        const int unroll = run >= 64 ? 2 : 4;
-        const uint64_t pb = (uint64_t)kFastThreads * unroll;
+        const uint64_t pb = (uint64_t)kFastThreads * kFastUnroll;
         if (!to_head && (P & (P - 1)) == 0 && run >= 128) {  // measured: linear stores win from 2 KB runs on
             uint32_t lp = 0;
             while ((1 << lp) < P) ++lp;
             dim3 g3((unsigned)((slab * (uint64_t)P + pb - 1) / pb), (unsigned)B);
-            if (unroll == 2)
-                hipLaunchKernelGGL((unpack_pow2_linear_store_kernel<2>), g3, dim3(kFastThreads), 0, st,
-                                   (const u32x4*)in, (u32x4*)out, (uint32_t)slab, lr, lp);
-            else
-                hipLaunchKernelGGL((unpack_pow2_linear_store_kernel<4>), g3, dim3(kFastThreads), 0, st,
-                                   (const u32x4*)in, (u32x4*)out, (uint32_t)slab, lr, lp);
+            hipLaunchKernelGGL((unpack_pow2_linear_store_kernel<kFastUnroll>), g3, dim3(kFastThreads), 0, st,
+                               (const u32x4*)in, (u32x4*)out, (uint32_t)slab, lr, lp);
             return launch_status();
         }
-        dim3 g2((unsigned)((slab + pb - 1) / pb), (unsigned)P, (unsigned)B);
+        const uint64_t chunks = (slab + pb - 1) / pb;
+        if (chunks * (uint64_t)P <= 0x7fffffffull) {
+            dim3 g2((unsigned)(chunks * (uint64_t)P), (unsigned)B);
 #define SP_FAST(TH, U)                                                                                   \
     hipLaunchKernelGGL((relayout_pow2_kernel<TH, U>), g2, dim3(kFastThreads), 0, st, (const u32x4*)in,    \
                        (u32x4*)out, (uint32_t)slab, lr, (uint32_t)S_l, (uint32_t)P)
-        if (to_head) { if (unroll == 2) SP_FAST(true, 2); else SP_FAST(true, 4); }
-        else         { if (unroll == 2) SP_FAST(false, 2); else SP_FAST(false, 4); }
+            if (to_head) SP_FAST(true, kFastUnroll); else SP_FAST(false, kFastUnroll);
 #undef SP_FAST
-        return launch_status();
+            return launch_status();
+        }
     }
     dim3 grid((unsigned)blocks), block(kThreads);
     const bool small = n_vec + per_block < 0xffffffffull;  // every index, tail included, fits u32
