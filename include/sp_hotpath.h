@@ -259,6 +259,14 @@ sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const 
                              int64_t T, int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Debug aid for the packed-document calls, which read cu_seqlens on the device only and so cannot reject a
+ * malformed array on the host: one small kernel writes to *flag (DEVICE int32, 4-byte aligned) 0 when
+ * cu_seqlens (n_docs + 1 entries) starts at 0, never decreases and ends at T, else a bit mask:
+ * 1 = cu[0] != 0, 2 = some cu[t+1] < cu[t], 4 = cu[n_docs] != T.  Nothing else depends on it; the caller
+ * reads the flag back when it wants to (the call itself does not synchronise). */
+sp_status sp_varlen_check_cu_seqlens(const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t* flag,
+                                     void* hip_stream);
+
 /* sp_attn_varlen_fwd for callers that cannot allocate device memory at all, not
  * even a workspace: code recorded into a HIP graph, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments minus the workspace, same kernels, same

@@ -23,7 +23,7 @@ SP_OK, SP_ERR_NULL, SP_ERR_SHAPE, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_A
 EXPORTS = (
     "sp_status_str", "sp_abi_version", "sp_pack_seq_to_head", "sp_unpack_head_to_seq", "sp_attn_fwd",
     "sp_attn_bwd_workspace_bytes", "sp_attn_varlen_fwd_workspace_bytes", "sp_attn_bwd", "sp_attn_bwd_stages",
-    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_varlen_fwd_static", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
+    "sp_attn_varlen_fwd", "sp_attn_varlen_bwd", "sp_attn_varlen_fwd_static", "sp_varlen_check_cu_seqlens", "sp_attn_fwd_seqlayout", "sp_attn_bwd_seqlayout",
     "sp_attn_block_fwd", "sp_attn_merge", "sp_attn_block_bwd_workspace_bytes", "sp_attn_block_bwd",
     "sp_rmsnorm_bwd_workspace_bytes", "sp_rmsnorm_fwd", "sp_rmsnorm_bwd", "sp_rope", "sp_swiglu_fwd", "sp_swiglu_bwd",
 )
@@ -43,10 +43,16 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_27089_amd.build` "
+    _lib = open_library(LIB_PATH)
+    return _lib
+
+
+def open_library(path: str) -> ctypes.CDLL:
+    """Load a build of the library and declare its entry points (tests compare two builds through this)."""
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2604_27089_amd.build` "
                           "(there is no CPU or PyTorch fallback)")
-    L = ctypes.CDLL(LIB_PATH)
+    L = ctypes.CDLL(path)
     c = ctypes
     vp, i64, i32, f32, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_float, c.c_size_t
     L.sp_status_str.restype = c.c_char_p; L.sp_status_str.argtypes = [c.c_int]
@@ -80,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.sp_attn_varlen_fwd.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_attn_varlen_fwd_static.restype = c.c_int
     L.sp_attn_varlen_fwd_static.argtypes = [vp] * 6 + [i32, i32, i64, i32, i32, i32, f32, vp]
+    L.sp_varlen_check_cu_seqlens.restype = c.c_int
+    L.sp_varlen_check_cu_seqlens.argtypes = [vp, i32, i64, vp, vp]
     L.sp_attn_varlen_bwd.restype = c.c_int
     L.sp_attn_varlen_bwd.argtypes = [vp] * 10 + [i32, i32, i64, i32, i32, i32, f32, vp, sz, vp]
     L.sp_rmsnorm_bwd_workspace_bytes.restype = sz
@@ -94,7 +102,6 @@ def lib() -> ctypes.CDLL:
     L.sp_swiglu_fwd.argtypes = [vp, vp, vp, i64, vp]
     L.sp_swiglu_bwd.restype = c.c_int
     L.sp_swiglu_bwd.argtypes = [vp] * 5 + [i64, vp]
-    _lib = L
     return L
 
 
@@ -357,6 +364,17 @@ def sp_attn_varlen_fwd_static(q, k, v, cu_seqlens, o, lse, max_seqlen: int = 0, 
                                            int(max_seqlen), T, Hq, Hkv, D, float(softmax_scale), _stream(stream)),
            "sp_attn_varlen_fwd_static")
     return o, lse
+
+
+def sp_varlen_check_cu_seqlens(cu_seqlens, T: int, flag=None, stream=None):
+    """Debug aid: returns a device int32 tensor holding 0 if cu_seqlens is well formed for T rows, else a bit
+    mask (1: cu[0] != 0, 2: decreasing somewhere, 4: cu[-1] != T).  Does not synchronise."""
+    n_docs = _docs(cu_seqlens)
+    flag = _new(stream, (1,), torch.int32, cu_seqlens.device) if flag is None else flag
+    _expect(flag, (1,), torch.int32, "flag")
+    _check(lib().sp_varlen_check_cu_seqlens(_ptr(cu_seqlens), n_docs, int(T), _ptr(flag), _stream(stream)),
+           "sp_varlen_check_cu_seqlens")
+    return flag
 
 
 def sp_attn_varlen_bwd(q, k, v, o, lse, do, cu_seqlens, max_seqlen: int = 0, softmax_scale: float = 0.0,

@@ -139,6 +139,25 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const void* p) {
 }
 
 // ---------------------------------------------------------------------------
+// Hazard-proof build (-DSP_PADDED_MFMA): every assembly MFMA below is preceded by
+// a full wait for outstanding LDS reads plus the two wait states a vector-ALU
+// write needs before an MFMA reads it, and followed by the wait states after
+// which any instruction may read its result; every partial LDS wait becomes a
+// full one.  The arithmetic and its order are unchanged, so the padded build
+// must give the regular build's bits: a test compares the two, which checks the
+// hand-counted waits and instruction spacing of the regular build.
+// ---------------------------------------------------------------------------
+#ifdef SP_PADDED_MFMA
+#define SP_MFMA_PRE "s_waitcnt lgkmcnt(0)\n\ts_nop 1\n\t"
+#define SP_MFMA_POST "\n\ts_nop 15\n\ts_nop 7"
+#define SP_LGKM(N) 0
+#else
+#define SP_MFMA_PRE ""
+#define SP_MFMA_POST ""
+#define SP_LGKM(N) (N)
+#endif
+
+// ---------------------------------------------------------------------------
 // Asynchronous LDS operand reads with explicit waits.
 //
 // The compiler waits for ALL outstanding LDS reads before the first use of any
@@ -168,101 +187,74 @@ __device__ __forceinline__ u32x2 lds_async_tr16(uint32_t addr) {
 }
 template <int N>
 __device__ __forceinline__ void lds_wait(u32x4& x) {
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(SP_LGKM(N)));
 }
 template <int N>
 __device__ __forceinline__ void lds_wait(u32x2& x, u32x2& y) {
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(SP_LGKM(N)));
 }
 
 // ---------------------------------------------------------------------------
-// MFMA pinned to vector registers.
+// Assembly MFMAs for the hand-scheduled backward kernels.
 //
 // In a kernel that may use more than 256 registers the compiler is free to put
 // any MFMA accumulator into the accumulation registers, and does so even for
 // tiles the vector ALU has to read and seed, paying a move per register each
-// way.  These two helpers issue the MFMA as opaque assembly whose accumulator
-// is constrained to vector registers.  The compiler then no longer knows the
-// instruction is an MFMA, so the caller owns the data hazards:
-//   - mfma32_v results may be read by non-MFMA instructions only after
-//     mfma_results_ready(...), which spends the wait states an 8- or 16-pass
-//     MFMA needs before its destination is readable (and ties the values so no
-//     use can be scheduled before it);
-//   - operands written by vector-ALU instructions need two wait states before
-//     the MFMA.  The compiler may park resident operands in accumulation
-//     registers and copy them back right in front of the assembly, so the
-//     helpers always spend those two wait states themselves (s_nop 1);
+// way; issued as assembly, the accumulator is constrained to the register file
+// the kernel wants it in.  The compiler then no longer knows the instruction is
+// an MFMA, so the caller owns the data hazards.  Those kernels run one wave per
+// SIMD and are bound by how many instructions that lone wave can issue, so the
+// helpers carry no padding in the regular build; the callers guarantee that
+//   - no vector-ALU instruction writes an operand within the two instructions
+//     before the MFMA (operands come from LDS reads, from earlier MFMAs, or from
+//     arithmetic done at least one operand slot earlier);
+//   - the vector ALU reads an MFMA's result only after enough later instructions
+//     have issued to cover the 8-pass MFMA's result latency (in the kernels: two
+//     independent MFMAs, or the vector-ALU chunk of an earlier step);
 //   - back-to-back MFMAs on the same accumulator are interlocked by hardware.
 // MFMAs ignore the EXEC mask: code that contains them must only be skipped by a
 // truly scalar branch, so every wave-uniform condition guarding such code has
 // to be built from scalar values (readfirstlane anything loaded per lane).
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_v(f32x16& acc, const u32x4& a, const u32x4& b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-// first MFMA of a chain: the accumulator starts from zero
-__device__ __forceinline__ void mfma32_v0(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
-}
-
-// ---------------------------------------------------------------------------
-// Unpadded assembly MFMAs for the hand-scheduled backward kernels.
-//
-// Those kernels run one wave per SIMD and are bound by how many instructions
-// that lone wave can issue, so these helpers carry no padding.  The callers
-// guarantee that no vector-ALU instruction writes an operand within the two
-// instructions before the MFMA (operands come from LDS reads, from earlier
-// MFMAs, or from arithmetic done at least one operand slot earlier), and the
-// vector ALU reads MFMA results only after results_ready2.  Volatile assembly
-// statements keep their order, which is what orders an MFMA after the wait
-// that covers its operands.  W >= 0: that wait rides in the same statement.
+// Volatile assembly statements keep their order, which is what orders an MFMA
+// after the wait that covers its operands.  W >= 0: that wait rides in the same
+// statement.
 //   mfma_v  : accumulator in vector registers       mfma_vc : ... starting from another tile
 //   mfma_a  : accumulator in accumulation registers
 //   *_ab    : the B operand lives in accumulation registers (resident operands)
 // ---------------------------------------------------------------------------
 template <int W>
 __device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\t" SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "v"(b));
 }
 template <int W>
 __device__ __forceinline__ void mfma_v(f32x16& acc, const u32x4& a, const u32x4& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\t" SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+    asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" SP_MFMA_POST : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
 }
 __device__ __forceinline__ void mfma_vc(f32x16& acc, const u32x4& a, const u32x4& b, const f32x16& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
+    asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" SP_MFMA_POST : "=&v"(acc) : "v"(a), "v"(b), "v"(c));
 }
 __device__ __forceinline__ void mfma_a(f32x16& acc, const u32x4& a, const u32x4& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+a"(acc) : "v"(a), "v"(b));
 }
 template <int W>
 __device__ __forceinline__ void mfma_a_w(f32x16& acc, const u32x4& a, const u32x4& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\t" SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+a"(acc) : "v"(a), "v"(b), "n"(W));
+    else asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+a"(acc) : "v"(a), "v"(b));
 }
 template <int W>
 __device__ __forceinline__ void mfma_v_ab(f32x16& acc, const u32x4& a, const bf16x8& b) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\t" SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "a"(b), "n"(W));
+    else asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" SP_MFMA_POST : "+v"(acc) : "v"(a), "a"(b));
 }
 template <int W>
 __device__ __forceinline__ void mfma_vc_ab(f32x16& acc, const u32x4& a, const bf16x8& b, const f32x16& c) {
-    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%4)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(c), "n"(W));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(c));
-}
-// MFMA results in vector registers may be read by other instructions after this
-__device__ __forceinline__ void results_ready2(f32x16& a, f32x16& b) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
+    if constexpr (W >= 0) asm volatile("s_waitcnt lgkmcnt(%4)\n\t" SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" SP_MFMA_POST : "=&v"(acc) : "v"(a), "a"(b), "v"(c), "n"(W));
+    else asm volatile(SP_MFMA_PRE "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" SP_MFMA_POST : "=&v"(acc) : "v"(a), "a"(b), "v"(c));
 }
 // at most N of this wave's global loads (register and LDS destinations) are still in flight
 template <int N>
@@ -271,11 +263,11 @@ __device__ __forceinline__ void vmem_wait() { asm volatile("s_waitcnt vmcnt(%0)"
 // operands (the combination must not be scheduled before the wait).
 template <int N>
 __device__ __forceinline__ void lds_wait4(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(SP_LGKM(N)));
 }
 template <int N>
 __device__ __forceinline__ void lds_wait4(u32x2& a, u32x2& b, u32x2& c, u32x2& d) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(SP_LGKM(N)));
 }
 
 // Per-lane description of the DMA loads that fill one ROWS x D tile with NW waves.

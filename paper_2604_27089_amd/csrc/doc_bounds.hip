@@ -79,9 +79,34 @@ __global__ __launch_bounds__(256) void tile_rank_kernel(const int32_t* __restric
     }
 }
 
+// Debug aid: does a cu_seqlens array describe T rows?  One workgroup scans the n_docs + 1 entries and writes a
+// bit mask to *flag (0 = well formed): 1 cu[0] != 0, 2 some cu[t+1] < cu[t], 4 cu[n_docs] != T.  The attention
+// kernels never depend on it: they clamp what they read.
+__global__ __launch_bounds__(256) void check_cu_seqlens_kernel(const int32_t* __restrict__ cu, int32_t n_docs, int32_t T,
+                                                              int32_t* __restrict__ flag) {
+    __shared__ int32_t part[4];
+    int32_t bad = 0;
+    for (int32_t t = threadIdx.x; t <= n_docs; t += 256) {
+        const int32_t c = cu[t];
+        if (t == 0 && c != 0) bad |= 1;
+        if (t == n_docs && c != T) bad |= 4;
+        if (t < n_docs && cu[t + 1] < c) bad |= 2;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) bad |= __shfl_xor(bad, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = bad;
+    __syncthreads();
+    if (threadIdx.x == 0) *flag = part[0] | part[1] | part[2] | part[3];
+}
+
 }  // namespace
 
 namespace sp {
+
+sp_status launch_check_cu_seqlens(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* flag, hipStream_t st) {
+    hipLaunchKernelGGL(check_cu_seqlens_kernel, dim3(1), dim3(256), 0, st, cu_seqlens, n_docs, T, flag);
+    return launch_status();
+}
 
 sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* row_lo,
                             int32_t* row_hi, int32_t* work, int32_t* order_q, int32_t* order_k, hipStream_t st) {

@@ -341,6 +341,15 @@ sp_status sp_attn_varlen_fwd_static(const void* q, const void* k, const void* v,
                           (hipStream_t)hip_stream);
 }
 
+sp_status sp_varlen_check_cu_seqlens(const int32_t* cu_seqlens, int32_t n_docs, int64_t T, int32_t* flag,
+                                     void* hip_stream) {
+    if (n_docs < 0 || T < 0 || T >= (int64_t)1 << 31) return SP_ERR_SHAPE;
+    if (!cu_seqlens || !flag) return SP_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) != 0 || (reinterpret_cast<uintptr_t>(flag) & 3u) != 0)
+        return SP_ERR_ALIGN;
+    return sp::launch_check_cu_seqlens(cu_seqlens, n_docs, (int32_t)T, flag, (hipStream_t)hip_stream);
+}
+
 sp_status sp_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o,
                              const float* lse, const void* dO, void* dq, void* dk, void* dv,
                              const int32_t* cu_seqlens, int32_t n_docs, int32_t max_seqlen,

@@ -75,6 +75,8 @@ inline int32_t order_tiles(int64_t T) { return (int32_t)((T + kOrderTile - 1) / 
 // 2*order_tiles(T) int32, `order_q`, `order_k` receive order_tiles(T) int32 each.
 sp_status launch_doc_bounds(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* row_lo,
                             int32_t* row_hi, int32_t* work, int32_t* order_q, int32_t* order_k, hipStream_t st);
+// Debug aid: writes 0 to *flag if cu_seqlens is well formed for T rows, else a bit mask (doc_bounds.hip).
+sp_status launch_check_cu_seqlens(const int32_t* cu_seqlens, int32_t n_docs, int32_t T, int32_t* flag, hipStream_t st);
 // Grid of the forward and dQ kernels: x = head + Hq * batch, (y, z) = rank of the query tile in the order the
 // tiles are taken (rank = y + kRankY * z).  Workgroups are dispatched x first, so all heads and batch entries
 // of the longest tile go out before any shorter tile (a batch-major order would end with the long tiles of

@@ -171,6 +171,47 @@ def test_c4_dense_dO_sampled():
         assert torch.isfinite(t.float()).all()
 
 
+OTHER_SHARDS = [
+    # the head shards at P = 8 of the other models of Section 4's setup, at the length the benchmark times them
+    ("llama3.2-1b", 65536, 4, 1, 64),    # head dim 64
+    ("llama2-13b", 65536, 5, 5, 128),    # full attention: every query head has its own key/value head
+    ("llama3.2-3b", 65536, 3, 1, 128),   # three query heads on one key/value head
+]
+
+
+@pytest.mark.parametrize("name,S,Hq,Hkv,D", OTHER_SHARDS, ids=[t[0] for t in OTHER_SHARDS])
+def test_other_model_shards_full_size(name, S, Hq, Hkv, D):
+    """Full-size head shards of the other evaluated models: sampled rows of O, LSE and dQ, and with dO
+    non-zero on the sampled rows only, all of dK and dV."""
+    q, k, v, do = synth.attn_inputs(13, S, Hq, Hkv, D)
+    rows = sparse_rows(S, 24, 6)
+    do_s = np.zeros_like(do)
+    do_s[0, rows] = do[0, rows]
+    o, lse, dq, dk, dv = gpu_fwd_bwd(q, k, v, do_s)
+    qf, kf, vf, dof = (rn.widen_bf16(t[0]) for t in (q, k, v, do_s))
+    r = rs.attn_rows(qf, kf, vf, rows, dof)
+    dk_r, dv_r = rs.attn_cols(qf, kf, vf, dof, rows, r["lse"], r["delta"], np.arange(S))
+    idx = torch.from_numpy(rows).cuda()
+    err = check_o(host_f64(o[0, idx]), r["O"], name)
+    lerr = float(np.abs(host_f64(lse[0][:, idx]) - r["lse"]).max())
+    e = (grad_err(host_f64(dq[0, idx]), r["dQ"], "dQ"), grad_err(host_f64(dk)[0], dk_r, "dK"),
+         grad_err(host_f64(dv)[0], dv_r, "dV", abs_floor=0.0))
+    print(f"{name}: O {err:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+    assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
+    # dense dO: the tail window of key columns, every gradient finite
+    _, _, dq2, dk2, dv2 = gpu_fwd_bwd(q, k, v, do)
+    W = 160
+    tail = np.arange(S - W, S)
+    qf, kf, vf, dof = (rn.widen_bf16(t[0]) for t in (q, k, v, do))
+    rt = rs.attn_rows(qf, kf, vf, tail, dof)
+    dk_t, dv_t = rs.attn_cols(qf, kf, vf, dof, tail, rt["lse"], rt["delta"], tail)
+    e2 = (grad_err(host_f64(dq2[0, S - W:]), rt["dQ"], "dQ tail"), grad_err(host_f64(dk2[0, S - W:]), dk_t, "dK tail"),
+          grad_err(host_f64(dv2[0, S - W:]), dv_t, "dV tail", abs_floor=0.0))
+    assert max(e2) <= GRAD_REL_L2
+    for t in (dq2, dk2, dv2):
+        assert torch.isfinite(t.float()).all()
+
+
 def test_recompute_forward_is_bitwise_the_first_forward_at_128k():
     """Checkpoint-recompute (Section 3.2) runs the forward a second time in the backward pass: at the 128K
     shard the second run gives the first run's bits (fresh output buffers, other work in between)."""

@@ -129,3 +129,14 @@ def test_varlen_max_seqlen_is_only_a_hint(hint):
     dq_r, dk_r, dv_r, _ = rn.attn_varlen_bwd(qf, kf, vf, dof, cu)
     e = (grad_err(host_f64(dq), dq_r), grad_err(host_f64(dk), dk_r), grad_err(host_f64(dv), dv_r))
     assert max(e) <= GRAD_REL_L2, e
+
+
+def test_cu_seqlens_check_kernel():
+    """The debug check of a cu_seqlens array: well formed, wrong start, decreasing, wrong end, and all three."""
+    cases = [([0, 5, 5, 17, 300], 300, 0), ([1, 5, 300], 300, 1), ([0, 200, 100, 300], 300, 2), ([0, 100, 299], 300, 4),
+             ([3, 2, 1], 300, 7), ([0], 0, 0), (list(range(0, 70001, 7)), 70000, 0),
+             (list(range(0, 70001, 7))[:5000] + [1] + list(range(0, 70001, 7))[5001:], 70000, 2)]
+    for cu, T, want in cases:
+        flag = sp.sp_varlen_check_cu_seqlens(torch.tensor(cu, dtype=torch.int32, device="cuda"), T)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == want, (cu[:6], T, int(flag.item()), want)
