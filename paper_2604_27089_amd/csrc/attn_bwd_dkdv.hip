@@ -109,9 +109,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
         }
     }
     int wave_hi_min = S, wg_hi_max = S;
+    int khi_l[2] = {S, S};  // packed documents: one past the last row that may see this lane's keys (their document's end)
     if (VARLEN) {
         wave_hi_min = __builtin_amdgcn_readfirstlane(p.row_hi[(wkey0 < S ? wkey0 : S - 1)]);
         wg_hi_max = __builtin_amdgcn_readfirstlane(p.row_hi[(j0 + BNK - 1 < S ? j0 + BNK - 1 : S - 1)]);
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) {
+            const int key = wkey0 + 32 * kbk + lo;
+            khi_l[kbk] = p.row_hi[key < S ? key : S - 1];
+        }
     }
 
     f32x16 dkacc[2][NDB], dvacc[2][NDB];
@@ -395,15 +401,38 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
                 mfma_a(dkacc[1][db], dsp[1][c], bqt);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (t == 0) {
-                    // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
-                    if (cur_it <= it_mask_lo || cur_it >= it_mask_hi || step_no >= total) {  // rare
+                    // Causal / document mask: hidden positions get S' = -inf, i.e. P = 0.  Index by index only
+                    // on row tiles that reach the diagonal, on padding steps and, with packed documents, on the
+                    // row tile in which some key's document ends.  A key whose document ends before the row
+                    // tile is seen by none of its rows: all 16 of its S' take one select on a per-lane flag
+                    // (a select, not arithmetic: S' of such a pair may be anything, a NaN included).  A wave
+                    // whose keys straddle a document boundary is in that state for every row tile of the later
+                    // document; masked index by index, it held the whole workgroup back on its longest walk.
+                    bool elementwise = cur_it <= it_mask_lo || step_no >= total;
+                    if (VARLEN && cur_it >= it_mask_hi) {  // rows at or past the end of the first key's document
+                        const int q0 = cur_it * BMQ;
+                        const bool dead0 = khi_l[0] <= q0, dead1 = khi_l[1] <= q0;
+                        elementwise = elementwise ||
+                                      __builtin_amdgcn_ballot_w64((khi_l[0] > q0 && khi_l[0] < q0 + BMQ) ||
+                                                                  (khi_l[1] > q0 && khi_l[1] < q0 + BMQ)) != 0;
+                        if (!elementwise && __builtin_amdgcn_ballot_w64(dead0 || dead1) != 0) {
+                            asm volatile("" ::: "memory");  // keeps this a branch
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                sacc[0][r] = dead0 ? -__builtin_inff() : sacc[0][r];
+                                sacc[1][r] = dead1 ? -__builtin_inff() : sacc[1][r];
+                            }
+                        }
+                    }
+                    if (!VARLEN && cur_it >= it_mask_hi) elementwise = true;  // rows past the end of the sequence
+                    if (elementwise) {  // rare
                         asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
                         const int q0 = cur_it * BMQ;
                         const bool real = step_no < total;
 #pragma unroll
                         for (int kbk = 0; kbk < 2; ++kbk) {
                             const int key = wkey0 + 32 * kbk + (int)(__lane_id() & 31);
-                            const int key_hi = VARLEN ? p.row_hi[key < S ? key : S - 1] : S;  // one past the last row that may see the key
+                            const int key_hi = VARLEN ? khi_l[kbk] : S;  // one past the last row that may see the key
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int row = q0 + 8 * (r / 4) + 4 * (int)(__lane_id() >> 5) + (r % 4);

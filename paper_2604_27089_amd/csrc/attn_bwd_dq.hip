@@ -105,9 +105,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
         for (int r = 0; r < 16; ++r) { seed_s[qb][r] = ls; seed_p[qb][r] = dl; }
     }
     int wave_lo_max = 0, wg_lo_min = 0;
+    int rlo_l[2] = {0, 0};  // packed documents: the first key this lane's rows may see (their document's start)
     if (VARLEN) {
         wave_lo_max = __builtin_amdgcn_readfirstlane(p.row_lo[(wrow0 + RPW - 1 < S ? wrow0 + RPW - 1 : S - 1)]);
         wg_lo_min = __builtin_amdgcn_readfirstlane(p.row_lo[i0]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int row = wrow0 + 32 * qb + lo;
+            rlo_l[qb] = p.row_lo[row < S ? row : S - 1];
+        }
     }
 
     f32x16 dqacc[2][NDB];
@@ -339,15 +345,37 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(DqParams p) {
                 else mfma_v_ab<-1>(pacc[1], av[kk], doreg[1][kk]);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (kk == 0) {
-                    // causal / document mask: hidden positions get S' = -inf, i.e. P = 0
-                    if (step_no >= mask_from || step_no < mask_until) {  // rare
+                    // Causal / document mask: hidden positions get S' = -inf, i.e. P = 0.  Index by index only
+                    // on steps that reach the diagonal (or are padding) and, with packed documents, on the
+                    // step in which some row's document starts.  A row whose document starts after the step's
+                    // keys sees none of them: all 16 of its S' take one select on a per-lane flag (a select, not
+                    // arithmetic: S' of such a pair may be anything, a NaN included).  A wave whose rows
+                    // straddle a document boundary is in that state for every step of the earlier document;
+                    // masked index by index, it held the whole workgroup back on its longest walk.
+                    bool elementwise = step_no >= mask_from;
+                    if (VARLEN && step_no < mask_until) {  // some row's document starts at or after this step's keys
+                        const int j0 = cur_jt * BN;
+                        const bool dead0 = rlo_l[0] >= j0 + BN, dead1 = rlo_l[1] >= j0 + BN;
+                        elementwise = elementwise ||
+                                      __builtin_amdgcn_ballot_w64((rlo_l[0] > j0 && rlo_l[0] < j0 + BN) ||
+                                                                  (rlo_l[1] > j0 && rlo_l[1] < j0 + BN)) != 0;
+                        if (!elementwise && __builtin_amdgcn_ballot_w64(dead0 || dead1) != 0) {
+                            asm volatile("" ::: "memory");  // keeps this a branch
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                sacc[0][r] = dead0 ? -__builtin_inff() : sacc[0][r];
+                                sacc[1][r] = dead1 ? -__builtin_inff() : sacc[1][r];
+                            }
+                        }
+                    }
+                    if (elementwise) {  // rare
                         asm volatile("" ::: "memory");  // keeps this a branch (not selects executed on every step)
                         const int j0 = cur_jt * BN;
                         const bool real = step_no < total;
 #pragma unroll
                         for (int qb = 0; qb < 2; ++qb) {
                             const int row = wrow0 + 32 * qb + (int)(__lane_id() & 31);
-                            const int rlo = VARLEN ? p.row_lo[row < S ? row : S - 1] : 0;  // first key the row may see
+                            const int rlo = VARLEN ? rlo_l[qb] : 0;  // first key the row may see
                             const int rhi = row + p.off < p.Skv - 1 ? row + p.off : p.Skv - 1;  // and the last
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
