@@ -19,6 +19,9 @@ using namespace sp;
 
 
 // ------------------------------------------------------------------ delta
+// One 16-byte vector of O and dO per lane, D/8 lanes per (row, head).  The grid covers the padded row range
+// [0, S_pad): rows past the sequence only zero their slots of the per-row scalars (they are fetched by the
+// dK/dV kernel, never used unmasked).
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o,
                                                    const __bf16* __restrict__ dO,
@@ -27,60 +30,42 @@ __global__ __launch_bounds__(256) void delta_kernel(const __bf16* __restrict__ o
                                                    int32_t B, int32_t S, int32_t S_pad, int32_t Hq,
                                                    float inv_scale, RowMap map) {
     constexpr int LPV = D / 8;  // lanes per (row, head) vector, 16 bytes each
-    const int64_t n_vec = (int64_t)B * S * Hq;
-    const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;
+    const int64_t n_vec = (int64_t)B * S_pad * Hq;
+    const int64_t vec = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPV;  // (b*S_pad + i)*Hq + h
     const int part = threadIdx.x % LPV;
-    float acc = 0.f;
-    if (vec < n_vec) {
-        const int64_t bi_ = vec / Hq, b_ = bi_ / S;  // vec = (b*S + i)*Hq + h
-        const size_t at = (size_t)b_ * S * Hq * D + map.off((int32_t)(bi_ - b_ * S)) + (size_t)(vec - bi_ * Hq) * D + 8 * part;
-        const bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(o + at));
-        const bf16x8 b = as_bf16x8(*reinterpret_cast<const u32x4*>(dO + at));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
+    if (vec >= n_vec) return;  // whole (row, head) groups of lanes leave together: LPV divides 64
+    const int64_t bi = vec / Hq, b = bi / S_pad;
+    const int32_t h = (int32_t)(vec - bi * Hq), i = (int32_t)(bi - b * S_pad);
+    // the per-row accumulator seeds of the dK/dV kernel: per 32-row tile, 32 x -LSE/scale then 32 x -Delta
+    float* t = aux + ((b * Hq + h) * (S_pad / 32) + i / 32) * 64 + i % 32;
+    if (i >= S) {
+        if (part == 0) { t[0] = 0.f; t[32] = 0.f; }
+        return;
     }
+    const size_t at = (size_t)b * S * Hq * D + map.off(i) + (size_t)h * D + 8 * part;
+    const bf16x8 x = as_bf16x8(*reinterpret_cast<const u32x4*>(o + at));
+    const bf16x8 y = as_bf16x8(*reinterpret_cast<const u32x4*>(dO + at));
+    float acc = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)x[e] * (float)y[e];
 #pragma unroll
     for (int off = LPV / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (vec < n_vec && part == 0) {
-        const int64_t bi = vec / Hq;  // b*S + i
-        const int32_t h = (int32_t)(vec - bi * Hq);
-        const int64_t b = bi / S;
-        const int32_t i = (int32_t)(bi - b * S);
+    if (part == 0) {
         delta[(b * Hq + h) * S + i] = acc;
-        // the per-row accumulator seeds of the dK/dV kernel: per 32-row tile, 32 x -LSE/scale then 32 x -Delta
-        float* t = aux + ((b * Hq + h) * (S_pad / 32) + i / 32) * 64 + i % 32;
         t[0] = -lse[(b * Hq + h) * S + i] * inv_scale;
         t[32] = -acc;
     }
 }
 
-// zero the padding rows [S, S_pad) of the per-row scalars (they are fetched, never used unmasked)
-__global__ __launch_bounds__(256) void aux_pad_kernel(float* __restrict__ aux, int32_t BH, int32_t S,
-                                                     int32_t S_pad) {
-    const int32_t pad = S_pad - S;
-    const int64_t n = (int64_t)BH * pad;
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= n) return;
-    const int64_t bh = t / pad;
-    const int32_t i = S + (int32_t)(t - bh * pad);
-    float* dst = aux + (bh * (S_pad / 32) + i / 32) * 64 + i % 32;
-    dst[0] = 0.f;
-    dst[32] = 0.f;
-}
-
 template <int D, bool VARLEN>
 sp_status launch(const AttnArgs& a, hipStream_t st) {
     if (a.stages & SP_BWD_STAGE_DELTA) {
-        const int64_t lanes = (int64_t)a.B * a.S * a.Hq * (D / 8);
+        const int64_t lanes = (int64_t)a.B * a.S_pad * a.Hq * (D / 8);
         const int64_t blocks = (lanes + 255) / 256;
         if (blocks > 0x7fffffff) return SP_ERR_SHAPE;
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, st, (const __bf16*)a.o,
                            (const __bf16*)a.dO, a.lse, a.delta, a.aux, a.B, a.S, a.S_pad, a.Hq,
                            1.0f / a.scale, a.qmap);
-        if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
-        const int64_t npad = (int64_t)a.B * a.Hq * (a.S_pad - a.S);
-        hipLaunchKernelGGL(aux_pad_kernel, dim3((unsigned)((npad + 255) / 256)), dim3(256), 0, st, a.aux, a.B * a.Hq,
-                           a.S, a.S_pad);
         if (hipGetLastError() != hipSuccess) return SP_ERR_LAUNCH;
     }
     if (a.stages & SP_BWD_STAGE_DKDV) {

@@ -54,6 +54,7 @@ struct DkdvParams {
     const int32_t* row_hi;
     const int32_t* order;  // packed documents: key tiles in the order workgroups take them (or null)
     RowMap qmap, kvmap;
+    int32_t B, batch_fastest;
     int32_t S, Skv, off, S_pad, Hq, Hkv, G, n_ktiles, nsplit;  // S query rows, Skv keys; row i sees keys j <= i + off
     float scale, scale_log2;
 };
@@ -83,13 +84,19 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // earliest key tiles (most rows to visit) first; the nsplit workgroups that share a key tile are neighbours
     const int nsplit = SPLIT ? p.nsplit : 1;
-    int jt = SPLIT ? blockIdx.x / nsplit : blockIdx.x;
-    const int split = SPLIT ? blockIdx.x % nsplit : 0;
+    // Grid: (key tile x chunk, KV head, batch entry) for a single sequence; with several sequences the batch
+    // entry and KV head vary fastest instead, (KV head + Hkv * batch entry, key tile x chunk), so that every
+    // sequence's longest key tiles are dispatched before anybody's short ones (sequence by sequence, the last
+    // sequence's longest tile started when the grid was two thirds done: 16 x 4096 rows 710 -> 510 us).
+    const int chunk_id = p.batch_fastest ? blockIdx.y : blockIdx.x;
+    int jt = SPLIT ? chunk_id / nsplit : chunk_id;
+    const int split = SPLIT ? chunk_id % nsplit : 0;
     if (VARLEN && p.order) {  // longest tile first; clamped so that a bad entry cannot become a wild address
         const int v = __builtin_amdgcn_readfirstlane(p.order[jt]);
         jt = v < 0 ? 0 : (v < p.n_ktiles ? v : p.n_ktiles - 1);
     }
-    const int g = blockIdx.y, b = blockIdx.z;
+    const int g = p.batch_fastest ? blockIdx.x % p.Hkv : blockIdx.y;
+    const int b = p.batch_fastest ? blockIdx.x / p.Hkv : blockIdx.z;
     const int S = p.S, Skv = p.Skv;
     const __bf16* kb = p.k + ((size_t)b * Skv * p.Hkv + g) * D;
     const __bf16* vb = p.v + ((size_t)b * Skv * p.Hkv + g) * D;
@@ -519,7 +526,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(DkdvParams p) {
     // ---- write dK and dV: accumulator rows = keys, column = d ----
     if constexpr (SPLIT) {
         // fp32 partial sums of this chunk (dK unscaled); the reduction kernel adds the chunks in a fixed order
-        const size_t n_out = (size_t)gridDim.z * Skv * p.Hkv * D;
+        const size_t n_out = (size_t)p.B * Skv * p.Hkv * D;
         float* pk = p.part + (size_t)split * n_out;
         float* pv = pk + (size_t)nsplit * n_out;
 #pragma unroll
@@ -586,7 +593,10 @@ sp_status launch(const AttnArgs& a, hipStream_t st) {
     p.nsplit = a.dkdv_splits; p.part = a.dkdv_part;
     p.scale = a.scale; p.scale_log2 = a.scale * kLog2e;
     if (p.nsplit < 1 || (p.nsplit > 1 && !p.part)) return SP_ERR_WORKSPACE;
+    p.B = a.B;
+    p.batch_fastest = a.B > 1 && (int64_t)p.n_ktiles * p.nsplit <= 65535 && (int64_t)a.Hkv * a.B <= 0x7fffffff;
     dim3 grid(p.n_ktiles * p.nsplit, a.Hkv, a.B);
+    if (p.batch_fastest) grid = dim3(a.Hkv * a.B, p.n_ktiles * p.nsplit, 1);
     if (p.nsplit > 1) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN, true>), grid, dim3(kThreads), 0, st, p);
     else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, VARLEN, false>), grid, dim3(kThreads), 0, st, p);
     if (launch_status() != SP_OK) return SP_ERR_LAUNCH;

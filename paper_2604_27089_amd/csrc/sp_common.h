@@ -115,6 +115,10 @@ inline int32_t dkdv_split_count(int64_t B, int64_t S, int64_t Skv, int32_t Hq, i
     const int64_t steps_first = (longest + 31) / 32 * (Hq / Hkv);  // steps of the longest key tile
     int64_t n = 1;
     while (n < 8 && (2 * n + 1) * (2 * n + 1) * tiles * 10 <= 4 * 21 * steps_first) ++n;  // n <= sqrt(2.1 x) + 0.5
+    // Several sequences are dispatched batch entry fastest, longest tiles of every sequence first: there two
+    // workgroups per compute unit balance better than one even where the rule above says one chunk (256 tiles:
+    // 32 x 2048 rows 392 -> 336 us, 64 x 1024 rows 230 -> 220 us).
+    if (B > 1 && n * tiles < 512) n = (512 + tiles - 1) / tiles < 8 ? (512 + tiles - 1) / tiles : 8;
     const int64_t cap = (2048 + tiles - 1) / tiles;
     if (n > cap) n = cap;
     return n < 1 ? 1 : (int32_t)n;
