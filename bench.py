@@ -265,16 +265,18 @@ def main():
     detail["roofline_all"]["peak_tflops"] = MFMA_BF16_PEAK_TFLOPS
 
     def time_fn(fn, n, w=2):
+        """Median over n launches, each bracketed by its own pair of events (a stall of the box during one
+        launch, seen once as a 40 ms pause in a loop of 80 us kernels, then does not set the figure)."""
         for _ in range(w):
             fn()
-        a, b = ev(), ev()
         torch.cuda.synchronize()
-        a.record()
+        marks = []
         for _ in range(n):
-            fn()
-        b.record()
+            a, b = ev(), ev()
+            a.record(); fn(); b.record()
+            marks.append((a, b))
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / n
+        return float(np.median([a.elapsed_time(b) for a, b in marks]))
 
     if not args.no_extras:
         # checkpoint-recompute forward, timed alone
