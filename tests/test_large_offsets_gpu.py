@@ -1,0 +1,64 @@
+"""Tensors past 2^32 elements: every kernel's address arithmetic has to be 64-bit.
+
+The batch entries checked sit past element 2^31 and past element 2^32 of the
+query-side tensors, so an offset that wrapped at either width would read or write
+another entry (their contents differ: one device random stream over the whole
+tensor)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref_numpy as rn
+from oracle import ref_stream as rs
+from paper_2604_27089_amd import binding as sp
+from gpu_util import GRAD_REL_L2, LSE_MAX_ABS, check_o, grad_err, host_bits, host_f64, progress
+
+pytestmark = pytest.mark.gpu
+
+
+def test_attention_batch_past_2_to_32_elements():
+    B, S, Hq, Hkv, D = 2176, 2048, 8, 2, 128
+    assert B * S * Hq * D > 2 ** 32 and B * S * Hkv * D > 2 ** 30
+    g = torch.Generator(device="cuda").manual_seed(20)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    q, do = (torch.empty((B, S, Hq, D), **bf).normal_(generator=g) for _ in range(2))
+    k, v = (torch.empty((B, S, Hkv, D), **bf).normal_(generator=g) for _ in range(2))
+    progress(f"large batch: inputs on the device ({4 * q.numel() * 2 / 2**30:.1f} GiB query-side)")
+    o, lse = sp.sp_attn_fwd(q, k, v)
+    dq, dk, dv = sp.sp_attn_bwd(q, k, v, o, lse, do)
+    torch.cuda.synchronize()
+    progress("large batch: forward and backward done")
+    per_entry = S * Hq * D
+    picks = (0, 2 ** 31 // per_entry + 76, B - 1)
+    assert picks[1] * per_entry > 2 ** 31 and picks[2] * per_entry > 2 ** 32
+    for b in picks:
+        qh, kh, vh, doh = (rn.widen_bf16(host_bits(t[b])) for t in (q, k, v, do))
+        o_r, lse_r = rs.attn_fwd(qh, kh, vh)
+        # the backward's Delta comes from the bf16 O the kernels saw; the oracle uses its own exact O
+        dq_r, dk_r, dv_r, _ = rs.attn_bwd(qh, kh, vh, doh)
+        oerr = check_o(host_f64(o[b]), o_r, f"b={b}")
+        lerr = float(np.abs(host_f64(lse[b]) - lse_r).max())
+        e = [grad_err(host_f64(dq[b]), dq_r, f"dQ b={b}"), grad_err(host_f64(dk[b]), dk_r, f"dK b={b}"),
+             grad_err(host_f64(dv[b]), dv_r, f"dV b={b}", abs_floor=0.0)]
+        progress(f"large batch b={b}: O {oerr:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+        assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
+
+
+@pytest.mark.parametrize("B,S_l", [(1, 2 ** 19), (2, 2 ** 18)])
+def test_relayout_past_2_to_32_elements(B, S_l):
+    H, D, P = 64, 128, 8
+    assert B * S_l * H * D == 2 ** 32
+    g = torch.Generator(device="cuda").manual_seed(21)
+    x = torch.randint(-32768, 32767, (B, S_l, H, D), dtype=torch.int16, device="cuda", generator=g)
+    y = sp.sp_pack_seq_to_head(x, P)
+    back = sp.sp_unpack_head_to_seq(y, P)
+    assert y.shape == (B, P * S_l, H // P, D)
+    assert torch.equal(back, x)
+    del back
+    rng = np.random.default_rng(1)
+    h = H // P
+    for b in range(B):
+        for p in range(P):
+            for s in [0, S_l - 1] + [int(t) for t in rng.integers(0, S_l, 6)]:
+                # the index map, row by row: out[b, p*S_l + s, j, :] = in[b, s, p*h + j, :]
+                assert np.array_equal(y[b, p * S_l + s].cpu().numpy(), x[b, s, p * h:(p + 1) * h].cpu().numpy())
