@@ -62,3 +62,37 @@ def test_relayout_past_2_to_32_elements(B, S_l):
             for s in [0, S_l - 1] + [int(t) for t in rng.integers(0, S_l, 6)]:
                 # the index map, row by row: out[b, p*S_l + s, j, :] = in[b, s, p*h + j, :]
                 assert np.array_equal(y[b, p * S_l + s].cpu().numpy(), x[b, s, p * h:(p + 1) * h].cpu().numpy())
+
+
+def test_packed_documents_past_2_to_32_elements():
+    """4.2 million packed rows: more tiles than the longest-first ordering ranks (the kernels then take the
+    tiles in plain order), query-side tensors past 2^32 elements; the first document, one past element 2^31
+    and the last against the oracle on that document alone."""
+    from paper_2604_27089_amd import synth
+    T, Hq, Hkv, D = 2 ** 22 + 777, 8, 2, 128
+    assert T * Hq * D > 2 ** 32 and (T + 255) // 256 > 16384
+    lengths = synth.doc_lengths(3, T, mean=2048.0, hi=4096)
+    cu = synth.cu_seqlens_from_lengths(lengths)
+    g = torch.Generator(device="cuda").manual_seed(22)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    q, do = (torch.empty((T, Hq, D), **bf).normal_(generator=g) for _ in range(2))
+    k, v = (torch.empty((T, Hkv, D), **bf).normal_(generator=g) for _ in range(2))
+    cud = torch.from_numpy(np.asarray(cu, np.int32)).cuda()
+    progress(f"large packed batch: {len(lengths)} documents, longest {max(lengths)}")
+    o, lse = sp.sp_attn_varlen_fwd(q, k, v, cud, max_seqlen=max(lengths))
+    dq, dk, dv = sp.sp_attn_varlen_bwd(q, k, v, o, lse, do, cud, max_seqlen=max(lengths))
+    torch.cuda.synchronize()
+    progress("large packed batch: forward and backward done")
+    mid = int(np.searchsorted(cu, 2 ** 31 // (Hq * D) + 5000, side="right"))
+    assert int(cu[mid]) * Hq * D > 2 ** 31
+    for d in (0, mid, len(lengths) - 1):
+        a, b = int(cu[d]), int(cu[d + 1])
+        qh, kh, vh, doh = (rn.widen_bf16(host_bits(t[a:b])) for t in (q, k, v, do))
+        o_r, lse_r = rs.attn_fwd(qh, kh, vh)
+        dq_r, dk_r, dv_r, _ = rs.attn_bwd(qh, kh, vh, doh)
+        oerr = check_o(host_f64(o[a:b]), o_r, f"doc {d}")
+        lerr = float(np.abs(host_f64(lse[:, a:b]) - lse_r).max())
+        e = [grad_err(host_f64(dq[a:b]), dq_r, f"dQ doc {d}"), grad_err(host_f64(dk[a:b]), dk_r, f"dK doc {d}"),
+             grad_err(host_f64(dv[a:b]), dv_r, f"dV doc {d}", abs_floor=0.0)]
+        progress(f"large packed batch doc {d} rows [{a},{b}): O {oerr:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+        assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
