@@ -96,3 +96,36 @@ def test_packed_documents_past_2_to_32_elements():
              grad_err(host_f64(dv[a:b]), dv_r, f"dV doc {d}", abs_floor=0.0)]
         progress(f"large packed batch doc {d} rows [{a},{b}): O {oerr:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
         assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
+
+
+def test_sequence_of_half_a_million_rows():
+    """One sequence four times the longest configured one, ragged: 2050 query tiles and key tiles per head,
+    8199 key steps for the last rows.  Sampled rows for O, LSE and dQ; dO lives on the sampled rows only, so
+    the oracle gives all of dK and dV from them while the kernels do a dense backward's work."""
+    S, Hq, Hkv, D = 2 ** 19 + 421, 2, 1, 128
+    g = torch.Generator(device="cuda").manual_seed(23)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    qd, do_full = (torch.empty((1, S, Hq, D), **bf).normal_(generator=g) for _ in range(2))
+    kd, vd = (torch.empty((1, S, Hkv, D), **bf).normal_(generator=g) for _ in range(2))
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, S - 422, S - 421, S - 2, S - 1], rng.integers(0, S, 12)])).astype(np.int64)
+    idx = torch.from_numpy(rows).cuda()
+    dod = torch.zeros_like(do_full)
+    dod[0, idx] = do_full[0, idx]
+    del do_full
+    progress(f"long sequence: S = {S}, inputs on the device")
+    o, lse = sp.sp_attn_fwd(qd, kd, vd)
+    dq, dk, dv = sp.sp_attn_bwd(qd, kd, vd, o, lse, dod)
+    torch.cuda.synchronize()
+    progress("long sequence: forward and backward done")
+    qf, kf, vf, dof = (rn.widen_bf16(host_bits(t[0])) for t in (qd, kd, vd, dod))
+    r = rs.attn_rows(qf, kf, vf, rows, dof)
+    dk_r, dv_r = rs.attn_cols(qf, kf, vf, dof, rows, r["lse"], r["delta"], np.arange(S))
+    oerr = check_o(host_f64(o[0, idx]), r["O"], "long sequence")
+    lerr = float(np.abs(host_f64(lse[0][:, idx]) - r["lse"]).max())
+    e = [grad_err(host_f64(dq[0, idx]), r["dQ"], "dQ"), grad_err(host_f64(dk)[0], dk_r, "dK"),
+         grad_err(host_f64(dv)[0], dv_r, "dV", abs_floor=0.0)]
+    progress(f"long sequence: O {oerr:.2e} LSE {lerr:.2e} dQ {e[0]:.2e} dK {e[1]:.2e} dV {e[2]:.2e}")
+    assert lerr <= LSE_MAX_ABS and max(e) <= GRAD_REL_L2
+    mask = torch.ones(S, dtype=torch.bool, device="cuda"); mask[idx] = False
+    assert float(dq[0, mask].float().abs().max()) == 0.0  # rows without dO get exactly zero dQ
