@@ -15,7 +15,7 @@ LSE_MAX_ABS = 2e-4
 
 
 def progress(msg: str):
-    """A line into gpurun_out/test_progress.log (and stderr): a long CPU oracle pass says how far it is."""
+    """A line into the run's output folder (test_progress.log) and stderr: a long CPU oracle pass says how far it is."""
     import os, sys, time
     d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     try:
